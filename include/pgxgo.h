@@ -1,0 +1,143 @@
+/*
+ * pgxgo.h -- C ABI of the batched Go environment for AMD MI355X (gfx950).
+ *
+ * The library implements the environment API of the Pgx paper (arXiv 2303.17503,
+ * Fig. 2: init / step / observation / legal_action_mask / rewards / terminated /
+ * current_player) for the Go 9x9 and Go 19x19 games (Table 1; Appendix C, "Go").
+ * Every rule step runs in HIP kernels on the device; this header is the only
+ * boundary.  No type of any other library appears in a signature.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller (for example the
+ *     data_ptr() of a torch tensor).  The library never frees them.  Pointers without
+ *     that suffix are HOST pointers.
+ *   - All work is enqueued on the HIP stream given in pgxgo_opts.stream (NULL = the
+ *     default stream) and is asynchronous with respect to the host.  No entry point
+ *     synchronises the device except pgxgo_init (once) and pgxgo_sync.
+ *   - Every function returns PGXGO_OK (0) or a negative error code; nothing throws or
+ *     aborts.  An action that is illegal *in the game* is not an API error: it ends that
+ *     game, the offender gets -1 and the opponent +1.
+ *   - Point index p = row * N + col (row-major), action p places a stone on p,
+ *     action N*N is pass (Appendix C "Go", Action: the last action is pass),
+ *     action -1 leaves that environment untouched (an extension used for staggered starts).
+ *   - Rules: Tromp-Taylor area scoring, komi added to White (Appendix C "Go").  Where the
+ *     paper is silent: simple ko (the ban lasts one ply), suicide is illegal, a game ends
+ *     after two consecutive passes or max_steps plies, and is then scored by area.
+ */
+#ifndef PGXGO_H_
+#define PGXGO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PGXGO_OK 0
+#define PGXGO_EINVAL (-1) /* null pointer, unsupported board size, batch <= 0, pitch too small, buffer too small */
+#define PGXGO_EHIP (-2)   /* a HIP runtime call failed; see pgxgo_last_hip_error() */
+#define PGXGO_ENOMEM (-3) /* host allocation of the handle failed */
+
+typedef struct pgxgo_ctx* pgxgo_t; /* opaque host-side handle */
+
+typedef struct {
+  int32_t komi_x2;    /* twice the komi given to White; 15 = 7.5.  (The paper's default 6.5 is 13.) */
+  int32_t max_steps;  /* ply cap per game; 0 selects 2*N*N */
+  int32_t auto_reset; /* 1: a finished game is re-initialised within the same step call (Sec. 4.1) */
+  int32_t obs_pitch;  /* bytes between consecutive environments in observation buffers; 0 = N*N*17 (tight) */
+  int32_t mask_pitch; /* bytes between consecutive environments in legal-mask buffers; 0 = N*N+1 (tight) */
+  void* stream;       /* hipStream_t of the caller; NULL = default stream */
+} pgxgo_opts;
+
+/* Bytes of device memory pgxgo_init needs for `batch` games of size board_size (9 or 19);
+ * 0 if the arguments are invalid.  The caller allocates that many bytes, 256-byte aligned. */
+size_t pgxgo_state_bytes(int32_t batch, int32_t board_size);
+
+/* Fig. 2 "init": creates `batch` games on the empty board, Black to move, and draws for each
+ * game which player id (0/1) holds Black from bit 0 of hash(seed, 1, env, episode)
+ * (Fig. 2: current_player is drawn by a PRNG and is independent of the colour).
+ * state_dev/state_bytes: caller-owned device buffer of at least pgxgo_state_bytes() bytes that
+ * holds all game state until pgxgo_destroy.  opts may be NULL (defaults: komi 7.5, cap 2*N*N,
+ * no auto-reset, tight pitches, default stream).  Synchronises once before returning. */
+int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts,
+               void* state_dev, size_t state_bytes);
+
+/* Frees the host handle only (device buffers belong to the caller). */
+int pgxgo_destroy(pgxgo_t h);
+
+/* Starts a new episode in every environment (episode counters advance, seats are redrawn). */
+int pgxgo_reset(pgxgo_t h);
+
+/* Output buffers that pgxgo_step fills directly, so that no copy is needed afterwards.
+ *   mask_dev [batch][mask_pitch] uint8 0/1 : legal_action_mask of the player to move (Fig. 2)
+ *   obs_dev  [batch][obs_pitch]  uint8 0/1 : observation of the player to move, laid out
+ *            [N][N][17]: planes 2i / 2i+1 = mover's / opponent's stones i plies ago (i = 0..7),
+ *            plane 16 = 1 when Black is to move (Appendix C "Go", Observation)
+ *   rewards_dev [batch][2] float32, indexed by player id: +1 / -1 / 0 (Appendix C "Go", Reward);
+ *            non-zero only in the step call that ends a game
+ *   terminated_dev [batch] uint8 : 1 if the game ended in this step call (or had ended before,
+ *            without auto-reset)
+ * Any pointer may be NULL: mask/obs are then not written by step (pgxgo_legal_mask and
+ * pgxgo_observe still work), rewards/terminated go to internal arrays read by the getters. */
+int pgxgo_bind_outputs(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev);
+
+/* Fig. 2 "step": applies actions_dev[batch] (int32) to all games: legality gate, stone placement,
+ * chain merge, liberty count, capture, ko, history push, termination and area scoring,
+ * optional auto-reset, then the next mover's legal mask and observation.  With auto-reset the
+ * rewards/terminated of the finishing ply are returned together with the fresh game's mask and
+ * observation.  A game that ended earlier (no auto-reset) is frozen and reports zero rewards. */
+int pgxgo_step(pgxgo_t h, const int32_t* actions_dev);
+
+/* Uniform random legal actions (Sec. 4.1 random policy): actions_dev[e] = the k-th legal action in
+ * ascending index order, k = hash(seed, 0, e, t) mod legal_count, where
+ * mix(x): x^=x>>16; x*=0x7feb352d; x^=x>>15; x*=0x846ca68b; x^=x>>16 and
+ * hash(s,tag,e,t) = mix(mix(mix(s + 0x9E3779B9*(tag+1)) ^ e) ^ t) in uint32 arithmetic.
+ * start_t_dev (nullable, int32[batch]): environments with t < start_t_dev[e] get action -1. */
+int pgxgo_random_actions(pgxgo_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev);
+
+/* pgxgo_step followed by pgxgo_random_actions(seed, t, start_t_dev, next_actions_dev) on the new
+ * position, in one kernel launch.  next_actions_dev must not alias actions_dev. */
+int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev,
+                      int32_t* next_actions_dev);
+
+/* Getters for the current state; each enqueues one kernel or copy into the caller's buffer. */
+int pgxgo_legal_mask(pgxgo_t h, uint8_t* dst_dev /* [batch][mask_pitch] */);
+int pgxgo_observe(pgxgo_t h, uint8_t* dst_dev /* [batch][obs_pitch] */);
+int pgxgo_rewards(pgxgo_t h, float* dst_dev /* [batch][2], values of the last step call */);
+int pgxgo_terminated(pgxgo_t h, uint8_t* dst_dev /* [batch], values of the last step call */);
+int pgxgo_current_player(pgxgo_t h, uint8_t* dst_dev /* [batch] player id to move */);
+
+/* Canonical state for tests, checkpoints and search: any pointer may be NULL on export.
+ *   board [batch][N*N] int8 (0 empty, +1 black, -1 white); history [batch][8][N*N] int8,
+ *   history[.][0] = current position, zero before the game started; ko int32 (-1 = none);
+ *   to_play int8 (+1 black / -1 white); steps int32; passes int8; terminated uint8;
+ *   black_player uint8; episode uint32; illegal uint32 (count of illegal actions received). */
+int pgxgo_export_state(pgxgo_t h, int8_t* board_dev, int8_t* history_dev, int32_t* ko_dev, int8_t* to_play_dev,
+                       int32_t* steps_dev, int8_t* passes_dev, uint8_t* terminated_dev, uint8_t* black_player_dev,
+                       uint32_t* episode_dev, uint32_t* illegal_dev);
+/* All pointers required.  Positions must be legal Go positions (every chain has a liberty). */
+int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history_dev, const int32_t* ko_dev,
+                       const int8_t* to_play_dev, const int32_t* steps_dev, const int8_t* passes_dev,
+                       const uint8_t* terminated_dev, const uint8_t* black_player_dev, const uint32_t* episode_dev);
+
+/* Blocks the host until everything enqueued on the handle's stream has finished. */
+int pgxgo_sync(pgxgo_t h);
+
+/* Facts about the compiled kernels, for the harness. */
+int32_t pgxgo_boards_per_wavefront(int32_t board_size); /* 3 for 19, 6 for 9, 0 otherwise */
+int32_t pgxgo_num_actions(int32_t board_size);          /* N*N+1 (Table 1: 82 / 362) */
+int32_t pgxgo_obs_bytes(int32_t board_size);            /* N*N*17 (Table 1: 9x9x17 / 19x19x17) */
+
+const char* pgxgo_strerror(int code);
+int pgxgo_last_hip_error(void); /* hipError_t of the most recent PGXGO_EHIP on this thread, else 0 */
+
+/* Harness helper: cross-lane shift semantics of the target (lane i reads lane i-1 / i+1, zero at
+ * the wavefront ends).  Writes out_dev[0..63] = value seen from below, out_dev[64..127] = value
+ * seen from above, for in_dev[0..63].  Used by the tests to check the lane layout the kernels rely on. */
+int pgxgo_lane_shift_probe(const uint32_t* in_dev, uint32_t* out_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PGXGO_H_ */

@@ -1,0 +1,971 @@
+// pgxgo.hip -- batched Go environment step for AMD MI355X (gfx950, wave64), C ABI in include/pgxgo.h.
+//
+// What is computed: the Go environment of the Pgx paper (arXiv 2303.17503): Fig. 2 (init/step API,
+// legal_action_mask, observation, current_player), Table 1 (9x9x17 / 82 actions, 19x19x17 / 362 actions),
+// Appendix C "Go" (Tromp-Taylor area scoring, komi for White, 8x2 history planes + colour plane, pass is
+// the last action, rewards +1/-1/0), Sec. 4.1 (random policy, auto-reset on termination).
+//
+// How it is mapped to the machine (nothing of this is in the paper, whose implementation is XLA-generated):
+//   * One board row per lane.  A wavefront holds W = 63/(N+1) boards (3 at 19x19, 6 at 9x9): board j owns
+//     lanes j*(N+1)+1 .. j*(N+1)+N, and lanes j*(N+1) stay all-zero "sentinel rows", so a one-lane DPP
+//     wave shift moves every row to its north/south neighbour and brings zeros in from off the board.
+//   * Stones are row bitboards (bit c = column c).  East/west neighbours are register shifts, north/south
+//     neighbours are DPP shifts; a flood-fill step is ~7 VALU instructions for all W boards at once.
+//   * The state keeps, besides the stones, the set of stones whose chain has exactly one liberty
+//     ("atari sets").  With them captures, the ko test and the whole legal mask are stencils; only the
+//     chains touched by the move are re-flooded (the merged chain and at most four opposing neighbours).
+//   * History is stored point-major: 16 bits per point = 8 plies x (black, white), two points per dword,
+//     so a ply is one shift-and-insert per dword and the [N][N][17] byte observation is produced by
+//     building the 17-bit-per-point bit stream of a board in LDS and expanding 16 bits -> 16 bytes per
+//     lane with a multiply-mask, stored as aligned 16-byte vectors.
+//   * HBM layout: struct of arrays of 16-byte vectors, plane k holds dwords 4k..4k+3 of every row record,
+//     indexed [env*N + row], so every load/store instruction of a wavefront touches one contiguous run.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "pgxgo.h"
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+#define HIPCHK(expr)                                   \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) {                            \
+      g_last_hip = (int)e_;                            \
+      return PGXGO_EHIP;                               \
+    }                                                  \
+  } while (0)
+
+// ------------------------------------------------------------------------------------------------
+// geometry
+// ------------------------------------------------------------------------------------------------
+template <int N>
+struct Geo {
+  static constexpr int P = N * N;
+  static constexpr int A = P + 1;
+  static constexpr int STRIDE = N + 1;        // lanes per board, one of them the zero sentinel row
+  static constexpr int W = 63 / STRIDE;       // boards per wavefront
+  static constexpr int HD = (N + 1) / 2;      // history dwords per row, two points per dword
+  static constexpr int REC = HD + 6;          // + black, white, atari-black, atari-white, legal, spare
+  static constexpr int NQ = (REC + 3) / 4;    // 16-byte planes per row record
+  static constexpr uint32_t FULL = (1u << N) - 1u;
+  static constexpr int OBS = P * 17;          // observation bytes per board
+  static constexpr int ROWBITS = N * 17;      // observation bits contributed by one row
+  static constexpr int NR = (ROWBITS + 31) / 32;       // dwords of one row's bit string
+  static constexpr int NI = ROWBITS / 32 - 1;          // dwords 1..NI of the shifted string are never shared with another row
+  static constexpr int OBS_DW = ((OBS + 15 + 31) / 32 + 3) / 4 * 4;   // LDS dwords of one board's bit stream (+ up to 15 lead bits)
+  static constexpr int MASK_DW = ((A + 15 + 31) / 32 + 3) / 4 * 4;
+};
+
+// per-board scalars, one 16-byte record per environment
+//   x: ko point or -1     y: steps[0:16) | passes[16:18) | white_to_move[18] | terminated[19] | black_player[20]
+//   z: episode            w: illegal actions received
+struct Meta {
+  int ko, steps, passes, wtm, term, bp;
+  uint32_t episode, illegal;
+};
+__device__ __forceinline__ Meta unpack_meta(uint4 v) {
+  Meta m;
+  m.ko = (int)v.x;
+  m.steps = v.y & 0xFFFF; m.passes = (v.y >> 16) & 3; m.wtm = (v.y >> 18) & 1; m.term = (v.y >> 19) & 1; m.bp = (v.y >> 20) & 1;
+  m.episode = v.z; m.illegal = v.w;
+  return m;
+}
+__device__ __forceinline__ uint4 pack_meta(const Meta& m) {
+  uint4 v;
+  v.x = (uint32_t)m.ko;
+  v.y = (uint32_t)m.steps | ((uint32_t)m.passes << 16) | ((uint32_t)m.wtm << 18) | ((uint32_t)m.term << 19) | ((uint32_t)m.bp << 20);
+  v.z = m.episode; v.w = m.illegal;
+  return v;
+}
+
+// counter-based hash of (seed, tag, env, t); tag 0 = action draw, tag 1 = seat draw (t = episode)
+__device__ __forceinline__ uint32_t mixer(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du;
+  x ^= x >> 15; x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ uint32_t env_hash(uint32_t seed, uint32_t tag, uint32_t env, uint32_t t) {
+  return mixer(mixer(mixer(seed + 0x9E3779B9u * (tag + 1u)) ^ env) ^ t);
+}
+
+// ------------------------------------------------------------------------------------------------
+// cross-lane primitives.  All of them must be called with every lane of the wavefront active.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t from_lane_below(uint32_t x) {  // lane i receives lane i-1, lane 0 receives 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t x) {  // lane i receives lane i+1, lane 63 receives 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x130 /* wave_shl:1 */, 0xF, 0xF, true);
+}
+// all 4-neighbours of the set x (bits beyond column N-1 may be set; callers intersect with on-board sets)
+__device__ __forceinline__ uint32_t dilate(uint32_t x) { return (x << 1) | (x >> 1) | from_lane_below(x) | from_lane_above(x); }
+
+__device__ __forceinline__ bool any_in_board(bool pred, uint64_t seg) { return (__ballot(pred) & seg) != 0ull; }
+
+// number of set bits of a board-wide set given by its row words, saturated at 2
+__device__ __forceinline__ int count012(uint32_t w, uint64_t seg) {
+  uint64_t nz = __ballot(w != 0u) & seg;
+  uint64_t multi = __ballot((w & (w - 1u)) != 0u) & seg;
+  int c = __popcll(nz);
+  return (multi != 0ull || c >= 2) ? 2 : c;
+}
+
+// connected component(s) of `seed` inside S
+__device__ __forceinline__ uint32_t flood_plain(uint32_t seed, uint32_t S) {
+  uint32_t F = seed;
+  for (;;) {
+    uint32_t G = F | (dilate(F) & S);
+    bool ch = G != F;
+    F = G;
+    if (__ballot(ch) == 0ull) break;
+  }
+  return F;
+}
+
+// Chain of `seed` inside S and the class (0, 1, 2 = two or more) of its liberty count in E.
+// With EARLY the search of a board stops as soon as two liberties are known; F is then partial.
+template <bool EARLY>
+__device__ __forceinline__ void flood_libs(uint32_t seed, uint32_t S, uint32_t E, uint64_t seg, uint32_t& Fout, int& cls) {
+  uint32_t F = seed;
+  bool done = !any_in_board(seed != 0u, seg);
+  cls = 0;
+  for (;;) {
+    uint32_t D = dilate(F);
+    int c = count012(D & E, seg);
+    uint32_t G = F | (D & S);
+    bool chg = any_in_board(G != F, seg);
+    if (!done) {
+      if (EARLY && c == 2) { done = true; cls = 2; }
+      else if (!chg) { done = true; cls = c; }
+      else F = G;
+    }
+    if (__ballot(!done) == 0ull) break;
+  }
+  Fout = F;
+}
+
+// ------------------------------------------------------------------------------------------------
+// lane bookkeeping
+// ------------------------------------------------------------------------------------------------
+template <int N>
+struct Lane {
+  int lane, j, r, b;     // lane id, board slot in the wavefront, row, global environment index
+  bool valid;            // this lane holds a real row of a real board
+  bool boardok;          // slot j holds a real board (also true for its sentinel lane)
+  uint64_t seg;          // lanes of the rows of this lane's board
+  uint32_t full;         // FULL on valid lanes, else 0
+  __device__ __forceinline__ Lane(int wave, int B) {
+    using G = Geo<N>;
+    lane = threadIdx.x;
+    j = lane / G::STRIDE;
+    int rr = lane - j * G::STRIDE;
+    r = rr - 1;
+    b = wave * G::W + j;
+    boardok = (j < G::W) && (b < B);
+    valid = boardok && rr >= 1;
+    seg = (j < G::W) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
+    full = valid ? G::FULL : 0u;
+  }
+};
+
+template <int N>
+struct Row {                      // per-lane registers: one row of one board
+  uint32_t h[Geo<N>::HD];         // history halfwords, bit 2i = black i plies ago, bit 2i+1 = white
+  uint32_t bk, wt, ab, aw, legal; // stones, atari sets, legal points of the player to move
+};
+
+template <int N>
+__device__ __forceinline__ void load_row(const uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, Row<N>& R) {
+  using G = Geo<N>;
+  uint32_t rec[G::NQ * 4];
+#pragma unroll
+  for (int k = 0; k < G::NQ * 4; ++k) rec[k] = 0u;
+  if (L.valid) {
+    size_t idx = (size_t)L.b * N + L.r;
+#pragma unroll
+    for (int k = 0; k < G::NQ; ++k) {
+      uint4 v = planes[(size_t)k * rows_total + idx];
+      rec[4 * k] = v.x; rec[4 * k + 1] = v.y; rec[4 * k + 2] = v.z; rec[4 * k + 3] = v.w;
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) R.h[k] = rec[k];
+  R.bk = rec[G::HD]; R.wt = rec[G::HD + 1]; R.ab = rec[G::HD + 2]; R.aw = rec[G::HD + 3]; R.legal = rec[G::HD + 4];
+}
+
+template <int N>
+__device__ __forceinline__ void store_row(uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, const Row<N>& R) {
+  using G = Geo<N>;
+  uint32_t rec[G::NQ * 4];
+#pragma unroll
+  for (int k = 0; k < G::NQ * 4; ++k) rec[k] = 0u;
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) rec[k] = R.h[k];
+  rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw; rec[G::HD + 4] = R.legal;
+  if (L.valid) {
+    size_t idx = (size_t)L.b * N + L.r;
+#pragma unroll
+    for (int k = 0; k < G::NQ; ++k) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
+  }
+}
+
+// legal points of the player to move (Fig. 2 legal_action_mask, pass excluded): empty, not the ko point, and
+// next to an empty point, or to an own chain that is not in atari, or to an opposing chain that is
+template <int N>
+__device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R, int wtm, int ko) {
+  uint32_t E = L.full & ~(R.bk | R.wt);
+  uint32_t own = wtm ? R.wt : R.bk, opp = wtm ? R.bk : R.wt;
+  uint32_t aown = wtm ? R.aw : R.ab, aopp = wtm ? R.ab : R.aw;
+  uint32_t support = E | (own & ~aown) | (opp & aopp);
+  int kr = ko / N, kc = ko - kr * N;
+  uint32_t kobit = (ko >= 0 && L.r == kr) ? (1u << kc) : 0u;
+  return E & ~kobit & dilate(support);
+}
+
+// ------------------------------------------------------------------------------------------------
+// bit stream -> byte stream.  `bits` (LDS) holds bit (head+i) = byte i of the destination, head = the
+// destination's offset from the previous 16-byte boundary.  Whole aligned 16-byte groups are written as
+// vectors, the ragged ends byte by byte.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
+
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, uint8_t* dst, uint32_t nbytes, int lane) {
+  const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
+  uint8_t* base = dst - head;
+  const uint32_t total = head + nbytes;
+  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;
+  const uint16_t* b16 = (const uint16_t*)bits;
+  for (uint32_t m = m0 + lane; m < m1; m += 64u) {
+    uint32_t v = b16[m];
+    uint4 o;
+    o.x = spread4(v & 15u); o.y = spread4((v >> 4) & 15u); o.z = spread4((v >> 8) & 15u); o.w = spread4((v >> 12) & 15u);
+    *(uint4*)(base + 16u * m) = o;
+  }
+  if (lane < 32) {
+    uint32_t i = lane & 15u, pos;
+    bool ok;
+    if (lane < 16) { pos = i; ok = head != 0u && i >= head; }
+    else { pos = (m1 << 4) + i; ok = i < (total & 15u); }
+    if (ok) base[pos] = (uint8_t)((bits[pos >> 5] >> (pos & 31u)) & 1u);
+  }
+}
+
+// Legal mask bytes [N*N+1] and observation bytes [N][N][17] of every board of the wavefront.
+template <int N>
+__device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, int wtm, int wave, int B,
+                                             uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
+                                             uint32_t* lds_mask, uint32_t* lds_obs) {
+  using G = Geo<N>;
+  if (mask) {
+    for (int i = L.lane; i < G::W * G::MASK_DW; i += 64) lds_mask[i] = 0u;
+    __syncthreads();
+    if (L.valid) {
+      uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u);
+      uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
+      uint32_t* reg = lds_mask + L.j * G::MASK_DW;
+      atomicOr(&reg[q], R.legal << s);
+      if (s + N > 32u) atomicOr(&reg[q + 1], R.legal >> (32u - s));
+      if (L.r == 0) { uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
+    }
+    __syncthreads();
+    for (int jj = 0; jj < G::W; ++jj) {
+      int bb = wave * G::W + jj;
+      if (bb >= B) break;
+      emit_bytes(lds_mask + jj * G::MASK_DW, mask + (int64_t)bb * mask_pitch, G::A, L.lane);
+    }
+  }
+  if (obs) {
+    // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
+    // then the colour bit (Appendix C "Go", Observation); a row is N such pieces back to back.
+    uint32_t S[G::NR];
+#pragma unroll
+    for (int k = 0; k < G::NR; ++k) S[k] = 0u;
+    const uint32_t cb = wtm ? 0u : 1u;
+    const uint32_t swapmask = wtm ? 0x55555555u : 0u;
+#pragma unroll
+    for (int jd = 0; jd < G::HD; ++jd) {
+      uint32_t w = R.h[jd];
+      uint32_t x = (w ^ (w >> 1)) & swapmask;
+      w ^= x | (x << 1);
+      uint32_t lo17 = (w & 0xFFFFu) | (cb << 16);
+      uint32_t hi17 = (2 * jd + 1 < N) ? ((w >> 16) | (cb << 16)) : 0u;
+      uint32_t low32 = lo17 | (hi17 << 17), high2 = hi17 >> 15;
+      const int pos = 34 * jd, k = pos >> 5, sh = pos & 31;
+      S[k] |= low32 << sh;
+      if (k + 1 < G::NR) S[k + 1] |= sh ? ((low32 >> (32 - sh)) | (high2 << sh)) : high2;
+    }
+    {
+      uint4* z = (uint4*)lds_obs;
+      for (int i = L.lane; i < G::W * G::OBS_DW / 4; i += 64) z[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
+    __syncthreads();
+    if (L.valid) {
+      uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u);
+      uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
+      uint32_t* reg = lds_obs + L.j * G::OBS_DW + q;
+      // shifted string T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door
+      atomicOr(&reg[0], S[0] << s);
+#pragma unroll
+      for (int i = 1; i <= G::NR; ++i) {
+        uint32_t hi = (i < G::NR) ? S[i] : 0u;
+        uint32_t t = __funnelshift_l(S[i - 1], hi, s);
+        if (i <= G::NI) reg[i] = t;
+        else if (t) atomicOr(&reg[i], t);
+      }
+    }
+    __syncthreads();
+    for (int jj = 0; jj < G::W; ++jj) {
+      int bb = wave * G::W + jj;
+      if (bb >= B) break;
+      emit_bytes(lds_obs + jj * G::OBS_DW, obs + (int64_t)bb * obs_pitch, G::OBS, L.lane);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// the step kernel
+// ------------------------------------------------------------------------------------------------
+struct StepArgs {
+  uint4* planes;
+  uint4* meta;
+  const int32_t* actions;
+  float* rew;
+  uint8_t* term;
+  uint8_t* mask;
+  uint8_t* obs;
+  int64_t mask_pitch, obs_pitch;
+  int B;
+  uint32_t seed;
+  int komi_x2, max_steps, auto_reset;
+  // fused sampler
+  uint32_t sample_seed, sample_t;
+  const int32_t* start_t;
+  int32_t* next_actions;
+};
+
+template <int N>
+__device__ __forceinline__ void sample_action(const Lane<N>& L, uint32_t legal, uint32_t seed, uint32_t t, const int32_t* start_t,
+                                              int32_t* out, int* lds_tmp) {
+  using G = Geo<N>;
+  int cnt = __popc(legal);
+  __syncthreads();
+  lds_tmp[L.lane] = cnt;
+  __syncthreads();
+  int before = 0, total = 1;   // pass is always legal
+  if (L.valid) {
+    for (int i = 0; i < N; ++i) {
+      int v = lds_tmp[L.j * G::STRIDE + 1 + i];
+      total += v;
+      if (i < L.r) before += v;
+    }
+    bool wait = start_t && (int64_t)t < (int64_t)start_t[L.b];
+    int k = (int)(env_hash(seed, 0u, (uint32_t)L.b, t) % (uint32_t)total);
+    if (wait) { if (L.r == 0) out[L.b] = -1; }
+    else if (k == total - 1) { if (L.r == 0) out[L.b] = G::P; }
+    else if (k >= before && k < before + cnt) {
+      uint32_t w = legal;
+      for (int i = k - before; i > 0; --i) w &= w - 1u;
+      out[L.b] = L.r * N + (__ffs(w) - 1);
+    }
+  }
+}
+
+template <int N, bool SAMPLE>
+__global__ void __launch_bounds__(64) go_step_kernel(StepArgs a) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs[G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask[G::W * G::MASK_DW];
+  __shared__ int lds_tmp[64];
+  const int wave = blockIdx.x;
+  const Lane<N> L(wave, a.B);
+  const size_t rows_total = (size_t)a.B * N;
+
+  Row<N> R;
+  load_row<N>(a.planes, rows_total, L, R);
+  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  const int act = L.boardok ? a.actions[L.b] : -1;
+
+  // ---- a1/a2: decode the action and gate it with the mover's legal mask --------------------------------
+  const bool skip = !L.boardok || act == -1;
+  const bool frozen = !skip && m.term;
+  const bool live = !skip && !frozen;
+  const bool is_pass = live && act == G::P;
+  const bool on_board = live && act >= 0 && act < G::P;
+  int pr = on_board ? act / N : -100, pc = on_board ? act - (act / N) * N : 0;
+  uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
+  const bool playing = on_board && any_in_board((R.legal & pbit) != 0u, L.seg);
+  const bool illegal = live && !is_pass && !playing;
+  if (!playing) { pr = -100; pbit = 0u; }
+  const int wtm0 = m.wtm;
+
+  float rew0 = 0.f, rew1 = 0.f;
+
+  // ---- a3-a5: place the stone, capture, update the atari sets, ko ----------------------------------------
+  if (__ballot(playing) != 0ull) {
+    uint32_t own = wtm0 ? R.wt : R.bk, opp = wtm0 ? R.bk : R.wt;
+    uint32_t aown = wtm0 ? R.aw : R.ab, aopp = wtm0 ? R.ab : R.aw;
+    const uint32_t nbN = (L.valid && L.r == pr - 1) ? (1u << pc) : 0u;
+    const uint32_t nbS = (L.valid && L.r == pr + 1) ? (1u << pc) : 0u;
+    const uint32_t nbW = (L.valid && L.r == pr) ? ((1u << pc) >> 1) : 0u;
+    const uint32_t nbE = (L.valid && L.r == pr) ? ((2u << pc) & G::FULL) : 0u;
+    const uint32_t nb = nbN | nbS | nbW | nbE;
+    own |= pbit;
+    // opposing chains in atari that touch the new stone lose their last liberty
+    uint32_t cap = 0u;
+    const uint32_t capseed = nb & aopp;
+    if (__ballot(capseed != 0u) != 0ull) {
+      cap = flood_plain(capseed, aopp);
+      opp &= ~cap; aopp &= ~cap;
+      // own chains in atari next to the vacated points gain a liberty
+      uint32_t un = flood_plain(aown & dilate(cap), aown);
+      aown &= ~un;
+    }
+    const uint32_t E = L.full & ~(own | opp);
+    // the chain of the new stone
+    uint32_t M; int clsM;
+    flood_libs<false>(pbit, own, E, L.seg, M, clsM);
+    aown = (aown & ~M) | (clsM == 1 ? M : 0u);
+    // opposing neighbour chains that survive have lost the liberty just filled
+    const uint32_t seeds[4] = {nbN & opp, nbS & opp, nbW & opp, nbE & opp};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      if (__ballot(seeds[d] != 0u) != 0ull) {
+        uint32_t F; int cls;
+        flood_libs<true>(seeds[d], opp, E, L.seg, F, cls);
+        if (cls == 1) aopp |= F;
+      }
+    }
+    // simple ko: one stone taken by a lone stone that is left with a single liberty
+    const int ncap = count012(cap, L.seg), nM = count012(M, L.seg);
+    const bool capN = any_in_board((cap & nbN) != 0u, L.seg), capS = any_in_board((cap & nbS) != 0u, L.seg);
+    const bool capW = any_in_board((cap & nbW) != 0u, L.seg);
+    if (playing) {
+      const int p = pr * N + pc;
+      m.ko = (ncap == 1 && nM == 1 && clsM == 1) ? (capN ? p - N : capS ? p + N : capW ? p - 1 : p + 1) : -1;
+      R.bk = wtm0 ? opp : own; R.wt = wtm0 ? own : opp;
+      R.ab = wtm0 ? aopp : aown; R.aw = wtm0 ? aown : aopp;
+    }
+  }
+  const bool moved = playing || is_pass;
+  if (is_pass) { m.ko = -1; m.passes += 1; }
+  if (playing) m.passes = 0;
+  if (moved) {
+    m.steps += 1;
+    m.wtm ^= 1;
+    // ---- a6: history push -------------------------------------------------------------------------------
+#pragma unroll
+    for (int jd = 0; jd < G::HD; ++jd) {
+      uint32_t t = R.bk >> (2 * jd), u = R.wt >> (2 * jd);
+      uint32_t cur = (t & 1u) | ((u & 1u) << 1) | ((t & 2u) << 15) | ((u & 2u) << 16);
+      R.h[jd] = ((R.h[jd] << 2) & 0xFFFCFFFCu) | cur;
+    }
+  }
+
+  // ---- a7: termination and Tromp-Taylor area score ------------------------------------------------------
+  const bool score = moved && (m.passes >= 2 || m.steps >= a.max_steps);
+  if (__ballot(score) != 0ull) {
+    const uint32_t E = L.full & ~(R.bk | R.wt);
+    const uint32_t rb = flood_plain(E & dilate(R.bk), E);
+    const uint32_t rw = flood_plain(E & dilate(R.wt), E);
+    int diff = __popc(R.bk | (rb & ~rw)) - __popc(R.wt | (rw & ~rb));
+    __syncthreads();
+    lds_tmp[L.lane] = diff;
+    __syncthreads();
+    int sum = 0;
+    if (L.valid)
+      for (int i = 0; i < N; ++i) sum += lds_tmp[L.j * G::STRIDE + 1 + i];
+    if (score) {
+      int d = 2 * sum - a.komi_x2;   // komi counts for White
+      float s = d > 0 ? 1.f : (d < 0 ? -1.f : 0.f);
+      rew0 = m.bp == 0 ? s : -s;
+      rew1 = -rew0;
+    }
+  }
+  if (illegal) {  // the offender loses at once, the position stays
+    const int mover = wtm0 ? 1 - m.bp : m.bp;
+    rew0 = mover == 0 ? -1.f : 1.f;
+    rew1 = -rew0;
+    m.illegal += 1;
+  }
+  const bool ended = score || illegal;
+  if (ended) {
+    m.term = 1;
+    // ---- a8: auto-reset (Sec. 4.1) -------------------------------------------------------------------------
+    if (a.auto_reset) {
+#pragma unroll
+      for (int jd = 0; jd < G::HD; ++jd) R.h[jd] = 0u;
+      R.bk = R.wt = R.ab = R.aw = 0u;
+      m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
+      m.episode += 1;
+      m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
+    }
+  }
+  if (!skip && L.valid && L.r == 0) {
+    a.rew[2 * (size_t)L.b] = rew0; a.rew[2 * (size_t)L.b + 1] = rew1;
+    a.term[L.b] = (uint8_t)((ended || frozen) ? 1 : 0);
+  }
+
+  // ---- a9/a10: legal mask and observation of the player now to move --------------------------------------
+  R.legal = legal_row<N>(L, R, m.wtm, m.ko);
+  emit_outputs<N>(L, R, m.wtm, wave, a.B, a.mask, a.mask_pitch, a.obs, a.obs_pitch, lds_mask, lds_obs);
+
+  // ---- a11: store the state --------------------------------------------------------------------------------
+  if (!skip) {
+    store_row<N>(a.planes, rows_total, L, R);
+    if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+  }
+  if (SAMPLE) sample_action<N>(L, R.legal, a.sample_seed, a.sample_t, a.start_t, a.next_actions, lds_tmp);
+}
+
+// ------------------------------------------------------------------------------------------------
+// auxiliary kernels
+// ------------------------------------------------------------------------------------------------
+template <int N>
+__global__ void __launch_bounds__(64) go_emit_kernel(const uint4* planes, const uint4* meta, int B, uint8_t* mask, int64_t mask_pitch,
+                                                     uint8_t* obs, int64_t obs_pitch) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs[G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask[G::W * G::MASK_DW];
+  const int wave = blockIdx.x;
+  const Lane<N> L(wave, B);
+  Row<N> R;
+  load_row<N>(planes, (size_t)B * N, L, R);
+  Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  emit_outputs<N>(L, R, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask, lds_obs);
+}
+
+// new episode for every environment: empty board, Black to move, seat from the hash
+template <int N>
+__global__ void go_reset_kernel(uint4* planes, uint4* meta, float* rew, uint8_t* term, int B, uint32_t seed, int first) {
+  using G = Geo<N>;
+  const size_t rows_total = (size_t)B * N;
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < rows_total) {
+#pragma unroll
+    for (int k = 0; k < G::NQ; ++k) {
+      uint32_t rec[4] = {0u, 0u, 0u, 0u};
+      if (G::HD + 4 >= 4 * k && G::HD + 4 < 4 * k + 4) rec[G::HD + 4 - 4 * k] = G::FULL;   // every point is legal
+      planes[(size_t)k * rows_total + i] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+    }
+  }
+  if (i < (size_t)B) {
+    Meta m;
+    if (first) { m.episode = 0u; m.illegal = 0u; }
+    else { Meta old = unpack_meta(meta[i]); m.episode = old.episode + 1u; m.illegal = old.illegal; }
+    m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
+    m.bp = (int)(env_hash(seed, 1u, (uint32_t)i, m.episode) & 1u);
+    meta[i] = pack_meta(m);
+    rew[2 * i] = 0.f; rew[2 * i + 1] = 0.f; term[i] = 0;
+  }
+}
+
+// k-th legal action of the stored legal words, one thread per environment
+template <int N>
+__global__ void go_random_actions_kernel(const uint4* planes, int B, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* actions) {
+  using G = Geo<N>;
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  if (start_t && (int64_t)t < (int64_t)start_t[b]) { actions[b] = -1; return; }
+  constexpr int slot = G::HD + 4;
+  const uint32_t* words = (const uint32_t*)(planes + (size_t)(slot / 4) * ((size_t)B * N) + (size_t)b * N) + (slot & 3);
+  uint32_t w[N];
+  int total = 1;
+#pragma unroll
+  for (int r = 0; r < N; ++r) { w[r] = words[4 * r]; total += __popc(w[r]); }
+  int k = (int)(env_hash(seed, 0u, (uint32_t)b, t) % (uint32_t)total);
+  int pick = G::P;
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    int c = __popc(w[r]);
+    if (pick == G::P && k >= 0) {
+      if (k < c) {
+        uint32_t x = w[r];
+        for (int i = k; i > 0; --i) x &= x - 1u;
+        pick = r * N + (__ffs(x) - 1);
+        k = -1;
+      } else k -= c;
+    }
+  }
+  actions[b] = pick;
+}
+
+template <int N>
+__global__ void go_current_player_kernel(const uint4* meta, int B, uint8_t* dst) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  Meta m = unpack_meta(meta[b]);
+  dst[b] = (uint8_t)(m.wtm ? 1 - m.bp : m.bp);
+}
+
+struct CanonArgs {
+  int8_t* board; int8_t* history; int32_t* ko; int8_t* to_play; int32_t* steps; int8_t* passes;
+  uint8_t* terminated; uint8_t* black_player; uint32_t* episode; uint32_t* illegal;
+};
+
+template <int N>
+__global__ void __launch_bounds__(64) go_export_kernel(const uint4* planes, const uint4* meta, int B, CanonArgs c) {
+  using G = Geo<N>;
+  const Lane<N> L(blockIdx.x, B);
+  Row<N> R;
+  load_row<N>(planes, (size_t)B * N, L, R);
+  if (!L.valid) return;
+  const size_t cell0 = (size_t)L.b * G::P + (size_t)L.r * N;
+#pragma unroll
+  for (int col = 0; col < N; ++col) {
+    if (c.board) c.board[cell0 + col] = (int8_t)((int)((R.bk >> col) & 1u) - (int)((R.wt >> col) & 1u));
+    if (c.history) {
+      uint32_t hw = (R.h[col >> 1] >> ((col & 1) * 16)) & 0xFFFFu;
+      for (int i = 0; i < 8; ++i)
+        c.history[((size_t)L.b * 8 + i) * G::P + (size_t)L.r * N + col] = (int8_t)((int)((hw >> (2 * i)) & 1u) - (int)((hw >> (2 * i + 1)) & 1u));
+    }
+  }
+  if (L.r == 0) {
+    Meta m = unpack_meta(meta[L.b]);
+    if (c.ko) c.ko[L.b] = m.ko;
+    if (c.to_play) c.to_play[L.b] = (int8_t)(m.wtm ? -1 : 1);
+    if (c.steps) c.steps[L.b] = m.steps;
+    if (c.passes) c.passes[L.b] = (int8_t)m.passes;
+    if (c.terminated) c.terminated[L.b] = (uint8_t)m.term;
+    if (c.black_player) c.black_player[L.b] = (uint8_t)m.bp;
+    if (c.episode) c.episode[L.b] = m.episode;
+    if (c.illegal) c.illegal[L.b] = m.illegal;
+  }
+}
+
+// canonical arrays -> private state; the atari sets are rebuilt chain by chain
+template <int N>
+__global__ void __launch_bounds__(64) go_import_kernel(uint4* planes, uint4* meta, float* rew, uint8_t* term, int B, CanonArgs c) {
+  using G = Geo<N>;
+  const Lane<N> L(blockIdx.x, B);
+  Row<N> R;
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) R.h[k] = 0u;
+  R.bk = R.wt = R.ab = R.aw = R.legal = 0u;
+  Meta m;
+  m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0; m.bp = 0; m.episode = 0u; m.illegal = 0u;
+  if (L.boardok) {
+    Meta old = unpack_meta(meta[L.b]);
+    m.illegal = old.illegal;
+    m.ko = c.ko[L.b]; m.wtm = c.to_play[L.b] < 0 ? 1 : 0; m.steps = c.steps[L.b] & 0xFFFF; m.passes = c.passes[L.b] & 3;
+    m.term = c.terminated[L.b] ? 1 : 0; m.bp = c.black_player[L.b] & 1; m.episode = c.episode[L.b];
+  }
+  if (L.valid) {
+    const size_t cell0 = (size_t)L.b * G::P + (size_t)L.r * N;
+    for (int col = 0; col < N; ++col) {
+      int v = c.board[cell0 + col];
+      if (v > 0) R.bk |= 1u << col; else if (v < 0) R.wt |= 1u << col;
+      uint32_t hw = 0u;
+      for (int i = 0; i < 8; ++i) {
+        int hv = c.history[((size_t)L.b * 8 + i) * G::P + (size_t)L.r * N + col];
+        if (hv > 0) hw |= 1u << (2 * i); else if (hv < 0) hw |= 1u << (2 * i + 1);
+      }
+#pragma unroll
+      for (int k = 0; k < G::HD; ++k) if (k == (col >> 1)) R.h[k] |= hw << ((col & 1) * 16);
+    }
+  }
+  const uint32_t E = L.full & ~(R.bk | R.wt);
+  uint32_t visited = 0u;
+  for (;;) {
+    const uint32_t rest = (R.bk | R.wt) & ~visited;
+    const uint64_t has = __ballot(rest != 0u);
+    if (has == 0ull) break;
+    const uint64_t mine = has & L.seg;
+    const bool first = mine != 0ull && (__ffsll((long long)mine) - 1) == L.lane;
+    const uint32_t seed = first ? (rest & (0u - rest)) : 0u;
+    const bool black = any_in_board((seed & R.bk) != 0u, L.seg);
+    uint32_t F; int cls;
+    flood_libs<false>(seed, black ? R.bk : R.wt, E, L.seg, F, cls);
+    visited |= F;
+    if (cls == 1) { if (black) R.ab |= F; else R.aw |= F; }
+  }
+  R.legal = legal_row<N>(L, R, m.wtm, m.ko);
+  store_row<N>(planes, (size_t)B * N, L, R);
+  if (L.valid && L.r == 0) {
+    meta[L.b] = pack_meta(m);
+    rew[2 * (size_t)L.b] = 0.f; rew[2 * (size_t)L.b + 1] = 0.f; term[L.b] = (uint8_t)m.term;
+  }
+}
+
+__global__ void lane_shift_probe_kernel(const uint32_t* in, uint32_t* out) {
+  uint32_t x = in[threadIdx.x];
+  out[threadIdx.x] = from_lane_below(x);
+  out[64 + threadIdx.x] = from_lane_above(x);
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+template <int N>
+size_t state_bytes_for(int B, size_t* off_meta, size_t* off_rew, size_t* off_term) {
+  using G = Geo<N>;
+  size_t o = 0;
+  o += align_up((size_t)G::NQ * B * N * sizeof(uint4), 256);
+  if (off_meta) *off_meta = o;
+  o += align_up((size_t)B * sizeof(uint4), 256);
+  if (off_rew) *off_rew = o;
+  o += align_up((size_t)B * 2 * sizeof(float), 256);
+  if (off_term) *off_term = o;
+  o += align_up((size_t)B, 256);
+  return o;
+}
+
+}  // namespace
+
+struct pgxgo_ctx {
+  int B, N;
+  uint32_t seed;
+  int komi_x2, max_steps, auto_reset;
+  int64_t obs_pitch, mask_pitch;
+  hipStream_t stream;
+  uint4* planes;
+  uint4* meta;
+  float* rew_int;
+  uint8_t* term_int;
+  uint8_t* mask_out;
+  uint8_t* obs_out;
+  float* rew_out;
+  uint8_t* term_out;
+};
+
+namespace {
+
+template <int N>
+int launch_reset(pgxgo_ctx* h, int first) {
+  const size_t n = (size_t)h->B * N;
+  const int threads = 256;
+  const unsigned blocks = (unsigned)((n + threads - 1) / threads);
+  hipLaunchKernelGGL(go_reset_kernel<N>, dim3(blocks), dim3(threads), 0, h->stream, h->planes, h->meta, h->rew_out, h->term_out, h->B, h->seed,
+                     first);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+unsigned waves_for(int B) { return (unsigned)((B + Geo<N>::W - 1) / Geo<N>::W); }
+
+template <int N>
+int launch_emit(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {
+  hipLaunchKernelGGL(go_emit_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, mask, h->mask_pitch, obs,
+                     h->obs_pitch);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* next) {
+  StepArgs a;
+  a.planes = h->planes; a.meta = h->meta; a.actions = actions; a.rew = h->rew_out; a.term = h->term_out;
+  a.mask = h->mask_out; a.obs = h->obs_out; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
+  a.B = h->B; a.seed = h->seed; a.komi_x2 = h->komi_x2; a.max_steps = h->max_steps; a.auto_reset = h->auto_reset;
+  a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
+  if (sample) hipLaunchKernelGGL((go_step_kernel<N, true>), dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_kernel<N, false>), dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, a);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+int launch_random(pgxgo_ctx* h, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* actions) {
+  const int threads = 64;
+  hipLaunchKernelGGL(go_random_actions_kernel<N>, dim3((h->B + threads - 1) / threads), dim3(threads), 0, h->stream, h->planes, h->B, seed, t,
+                     start_t, actions);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+int launch_export(pgxgo_ctx* h, const CanonArgs& c) {
+  hipLaunchKernelGGL(go_export_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, c);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+int launch_import(pgxgo_ctx* h, const CanonArgs& c) {
+  hipLaunchKernelGGL(go_import_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->rew_out, h->term_out, h->B,
+                     c);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+#define DISPATCH_N(h, call19, call9) ((h)->N == 19 ? (call19) : (call9))
+
+}  // namespace
+
+extern "C" {
+
+size_t pgxgo_state_bytes(int32_t batch, int32_t board_size) {
+  if (batch <= 0) return 0;
+  if (board_size == 19) return state_bytes_for<19>(batch, nullptr, nullptr, nullptr);
+  if (board_size == 9) return state_bytes_for<9>(batch, nullptr, nullptr, nullptr);
+  return 0;
+}
+
+int32_t pgxgo_boards_per_wavefront(int32_t n) { return n == 19 ? Geo<19>::W : n == 9 ? Geo<9>::W : 0; }
+int32_t pgxgo_num_actions(int32_t n) { return (n == 19 || n == 9) ? n * n + 1 : 0; }
+int32_t pgxgo_obs_bytes(int32_t n) { return (n == 19 || n == 9) ? n * n * 17 : 0; }
+
+int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts, void* state_dev, size_t state_bytes) {
+  if (!out) return PGXGO_EINVAL;
+  *out = nullptr;
+  if (batch <= 0 || (board_size != 9 && board_size != 19) || !state_dev) return PGXGO_EINVAL;
+  if (((uintptr_t)state_dev & 255u) != 0) return PGXGO_EINVAL;
+  const int P = board_size * board_size;
+  pgxgo_opts o;
+  if (opts) o = *opts;
+  else { o.komi_x2 = 15; o.max_steps = 0; o.auto_reset = 0; o.obs_pitch = 0; o.mask_pitch = 0; o.stream = nullptr; }
+  if (o.max_steps == 0) o.max_steps = 2 * P;
+  if (o.max_steps < 1 || o.max_steps > 65535) return PGXGO_EINVAL;
+  if (o.obs_pitch == 0) o.obs_pitch = P * 17;
+  if (o.mask_pitch == 0) o.mask_pitch = P + 1;
+  if (o.obs_pitch < P * 17 || o.mask_pitch < P + 1) return PGXGO_EINVAL;
+  size_t off_meta, off_rew, off_term;
+  const size_t need = board_size == 19 ? state_bytes_for<19>(batch, &off_meta, &off_rew, &off_term)
+                                       : state_bytes_for<9>(batch, &off_meta, &off_rew, &off_term);
+  if (state_bytes < need) return PGXGO_EINVAL;
+  pgxgo_ctx* h = (pgxgo_ctx*)calloc(1, sizeof(pgxgo_ctx));
+  if (!h) return PGXGO_ENOMEM;
+  h->B = batch; h->N = board_size; h->seed = seed;
+  h->komi_x2 = o.komi_x2; h->max_steps = o.max_steps; h->auto_reset = o.auto_reset ? 1 : 0;
+  h->obs_pitch = o.obs_pitch; h->mask_pitch = o.mask_pitch;
+  h->stream = (hipStream_t)o.stream;
+  uint8_t* base = (uint8_t*)state_dev;
+  h->planes = (uint4*)base;
+  h->meta = (uint4*)(base + off_meta);
+  h->rew_int = (float*)(base + off_rew);
+  h->term_int = base + off_term;
+  h->mask_out = nullptr; h->obs_out = nullptr; h->rew_out = h->rew_int; h->term_out = h->term_int;
+  int rc = DISPATCH_N(h, launch_reset<19>(h, 1), launch_reset<9>(h, 1));
+  if (rc == PGXGO_OK) {
+    hipError_t e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) { g_last_hip = (int)e; rc = PGXGO_EHIP; }
+  }
+  if (rc != PGXGO_OK) { free(h); return rc; }
+  *out = h;
+  return PGXGO_OK;
+}
+
+int pgxgo_destroy(pgxgo_t h) {
+  if (!h) return PGXGO_EINVAL;
+  free(h);
+  return PGXGO_OK;
+}
+
+int pgxgo_reset(pgxgo_t h) {
+  if (!h) return PGXGO_EINVAL;
+  int rc = DISPATCH_N(h, launch_reset<19>(h, 0), launch_reset<9>(h, 0));
+  if (rc != PGXGO_OK) return rc;
+  if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
+  return PGXGO_OK;
+}
+
+int pgxgo_bind_outputs(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
+  if (!h) return PGXGO_EINVAL;
+  float* new_rew = rewards_dev ? rewards_dev : h->rew_int;
+  uint8_t* new_term = terminated_dev ? terminated_dev : h->term_int;
+  if (new_rew != h->rew_out) HIPCHK(hipMemcpyAsync(new_rew, h->rew_out, (size_t)h->B * 2 * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+  if (new_term != h->term_out) HIPCHK(hipMemcpyAsync(new_term, h->term_out, (size_t)h->B, hipMemcpyDeviceToDevice, h->stream));
+  h->rew_out = new_rew; h->term_out = new_term;
+  h->mask_out = mask_dev; h->obs_out = obs_dev;
+  if (mask_dev || obs_dev) return DISPATCH_N(h, launch_emit<19>(h, mask_dev, obs_dev), launch_emit<9>(h, mask_dev, obs_dev));
+  return PGXGO_OK;
+}
+
+int pgxgo_step(pgxgo_t h, const int32_t* actions_dev) {
+  if (!h || !actions_dev) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_step<19>(h, actions_dev, false, 0u, 0u, nullptr, nullptr), launch_step<9>(h, actions_dev, false, 0u, 0u, nullptr, nullptr));
+}
+
+int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* next_actions_dev) {
+  if (!h || !actions_dev || !next_actions_dev || next_actions_dev == actions_dev) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_step<19>(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev),
+                    launch_step<9>(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev));
+}
+
+int pgxgo_random_actions(pgxgo_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev) {
+  if (!h || !actions_dev) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_random<19>(h, seed, t, start_t_dev, actions_dev), launch_random<9>(h, seed, t, start_t_dev, actions_dev));
+}
+
+int pgxgo_legal_mask(pgxgo_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_emit<19>(h, dst_dev, nullptr), launch_emit<9>(h, dst_dev, nullptr));
+}
+
+int pgxgo_observe(pgxgo_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_emit<19>(h, nullptr, dst_dev), launch_emit<9>(h, nullptr, dst_dev));
+}
+
+int pgxgo_rewards(pgxgo_t h, float* dst_dev) {
+  if (!h || !dst_dev) return PGXGO_EINVAL;
+  if (dst_dev != h->rew_out) HIPCHK(hipMemcpyAsync(dst_dev, h->rew_out, (size_t)h->B * 2 * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+  return PGXGO_OK;
+}
+
+int pgxgo_terminated(pgxgo_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXGO_EINVAL;
+  if (dst_dev != h->term_out) HIPCHK(hipMemcpyAsync(dst_dev, h->term_out, (size_t)h->B, hipMemcpyDeviceToDevice, h->stream));
+  return PGXGO_OK;
+}
+
+int pgxgo_current_player(pgxgo_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXGO_EINVAL;
+  const int threads = 256;
+  if (h->N == 19) hipLaunchKernelGGL(go_current_player_kernel<19>, dim3((h->B + threads - 1) / threads), dim3(threads), 0, h->stream, h->meta, h->B, dst_dev);
+  else hipLaunchKernelGGL(go_current_player_kernel<9>, dim3((h->B + threads - 1) / threads), dim3(threads), 0, h->stream, h->meta, h->B, dst_dev);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+int pgxgo_export_state(pgxgo_t h, int8_t* board_dev, int8_t* history_dev, int32_t* ko_dev, int8_t* to_play_dev, int32_t* steps_dev,
+                       int8_t* passes_dev, uint8_t* terminated_dev, uint8_t* black_player_dev, uint32_t* episode_dev, uint32_t* illegal_dev) {
+  if (!h) return PGXGO_EINVAL;
+  CanonArgs c = {board_dev, history_dev, ko_dev, to_play_dev, steps_dev, passes_dev, terminated_dev, black_player_dev, episode_dev, illegal_dev};
+  return DISPATCH_N(h, launch_export<19>(h, c), launch_export<9>(h, c));
+}
+
+int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history_dev, const int32_t* ko_dev, const int8_t* to_play_dev,
+                       const int32_t* steps_dev, const int8_t* passes_dev, const uint8_t* terminated_dev, const uint8_t* black_player_dev,
+                       const uint32_t* episode_dev) {
+  if (!h || !board_dev || !history_dev || !ko_dev || !to_play_dev || !steps_dev || !passes_dev || !terminated_dev || !black_player_dev ||
+      !episode_dev)
+    return PGXGO_EINVAL;
+  CanonArgs c = {(int8_t*)board_dev, (int8_t*)history_dev, (int32_t*)ko_dev, (int8_t*)to_play_dev, (int32_t*)steps_dev, (int8_t*)passes_dev,
+                 (uint8_t*)terminated_dev, (uint8_t*)black_player_dev, (uint32_t*)episode_dev, nullptr};
+  int rc = DISPATCH_N(h, launch_import<19>(h, c), launch_import<9>(h, c));
+  if (rc != PGXGO_OK) return rc;
+  if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
+  return PGXGO_OK;
+}
+
+int pgxgo_sync(pgxgo_t h) {
+  if (!h) return PGXGO_EINVAL;
+  HIPCHK(hipStreamSynchronize(h->stream));
+  return PGXGO_OK;
+}
+
+const char* pgxgo_strerror(int code) {
+  switch (code) {
+    case PGXGO_OK: return "ok";
+    case PGXGO_EINVAL: return "invalid argument";
+    case PGXGO_EHIP: return "HIP runtime error";
+    case PGXGO_ENOMEM: return "out of host memory";
+    default: return "unknown error";
+  }
+}
+
+int pgxgo_last_hip_error(void) { return g_last_hip; }
+
+int pgxgo_lane_shift_probe(const uint32_t* in_dev, uint32_t* out_dev, void* stream) {
+  if (!in_dev || !out_dev) return PGXGO_EINVAL;
+  hipLaunchKernelGGL(lane_shift_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, in_dev, out_dev);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+"""GPU parity: the HIP path against the CPU oracle, bit-exact, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import positions as pos
+from paper_2303_17503_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2303_17503_amd as pg
+    pg.lib()   # fails loudly if the HIP library is not built
+
+
+def test_lane_shift_layout():
+    import paper_2303_17503_amd as pg
+    v = torch.arange(100, 164, dtype=torch.int32, device="cuda")
+    below, above = pg.lane_shift_probe(v)
+    torch.cuda.synchronize()
+    assert below.cpu().tolist() == [0] + list(range(100, 163))
+    assert above.cpu().tolist() == list(range(101, 164)) + [0]
+
+
+def test_initial_state_and_getters():
+    from gpu_common import Pair
+    for N, B in ((9, 7), (19, 5), (19, 64)):
+        p = Pair(B, N, seed=11, auto_reset=False, bind=False)
+        p.compare("init unbound")
+        p = Pair(B, N, seed=11, auto_reset=False, bind=True)
+        p.compare("init bound")
+
+
+def test_hand_built_scripts_on_gpu():
+    """All hand-written rule scripts at once, one environment each; shorter scripts idle with the skip action."""
+    from gpu_common import Pair
+    names = sorted(pos.SCRIPTS)
+    B, T = len(names), max(len(pos.SCRIPTS[n]["moves"]) for n in names)
+    p = Pair(B, 9, seed=1, auto_reset=False)
+    for t in range(T):
+        a = np.array([pos.idx(pos.SCRIPTS[n]["moves"][t]) if t < len(pos.SCRIPTS[n]["moves"]) else -1 for n in names], np.int32)
+        p.step(torch.as_tensor(a, device="cuda"), a)
+        p.compare(f"script ply {t}")
+    g = p.env.export_state()
+    board, ko, tp = g["board"].cpu().numpy(), g["ko"].cpu().numpy(), g["to_play"].cpu().numpy()
+    mask = p.gpu_mask()
+    for i, n in enumerate(names):
+        sc = pos.SCRIPTS[n]
+        assert board[i].tolist() == sc["board"], n
+        assert ko[i] == (-1 if sc["ko"] == -1 else sc["ko"][0] * 9 + sc["ko"][1]), n
+        assert tp[i] == sc["to_play"], n
+        for rc in sc.get("illegal_next", []):
+            assert mask[i, rc[0] * 9 + rc[1]] == 0, (n, rc)
+        for rc in sc.get("legal_next", []):
+            assert mask[i, rc[0] * 9 + rc[1]] == 1, (n, rc)
+
+
+@pytest.mark.parametrize("N,B,T,auto_reset", [(9, 256, 162, False), (9, 100, 400, True), (19, 64, 722, False), (19, 50, 900, True)])
+def test_rollout_every_env_every_ply(N, B, T, auto_reset):
+    """Sizes that span several wavefronts with a ragged last one (B not a multiple of boards per wavefront)."""
+    from gpu_common import Pair
+    p = Pair(B, N, seed=N + B, auto_reset=auto_reset)
+    p.rollout(N + B, 0, T, every=1, state_every=25)
+    s = p.orc.export_state()
+    assert s.episode.max() >= 1 if auto_reset else (s.terminated == 1).all()
+
+
+@pytest.mark.parametrize("N", [9, 19])
+def test_rollout_fused_sampler_and_unbound_getters(N):
+    from gpu_common import Pair
+    p = Pair(40, N, seed=5, auto_reset=True, bind=True)
+    p.rollout(5, 0, 300, every=1, state_every=50, fused=True)
+    q = Pair(10, N, seed=6, auto_reset=True, bind=False)
+    q.rollout(6, 0, 120, every=3, state_every=30)
+
+
+@pytest.mark.parametrize("obs_pitch,mask_pitch", [(6144, 368), (6137 + 3, 362 + 5)])
+def test_padded_and_misaligned_pitches(obs_pitch, mask_pitch):
+    from gpu_common import Pair
+    p = Pair(20, 19, seed=8, auto_reset=True, obs_pitch=obs_pitch, mask_pitch=mask_pitch)
+    p.obs.fill_(7); p.mask.fill_(7)
+    p.env.bind_outputs(p.mask, p.obs, p.rew, p.term)
+    p.rollout(8, 0, 150, every=1, state_every=50)
+    # bytes between the environments' records are never touched
+    assert (p.obs[:, 6137:] == 7).all() and (p.mask[:, 362:] == 7).all()
+
+
+def test_misaligned_output_base_pointers():
+    from gpu_common import Pair
+    import paper_2303_17503_amd as pg
+    B, N = 9, 9
+    p = Pair(B, N, seed=3, auto_reset=True, bind=False)
+    raw_o = torch.full((B * 1377 + 64,), 9, dtype=torch.uint8, device="cuda")
+    raw_m = torch.full((B * 82 + 64,), 9, dtype=torch.uint8, device="cuda")
+    for off in (1, 5, 16, 31):
+        ob = raw_o[off: off + B * 1377].view(B, 1377)
+        mk = raw_m[off: off + B * 82].view(B, 82)
+        raw_o.fill_(9); raw_m.fill_(9)
+        p.env.bind_outputs(mk, ob, None, None)
+        a = p.env.random_actions(3, off)
+        a_c = p.orc.random_actions(3, off)
+        p.step(a, a_c)
+        assert (ob.cpu().numpy().reshape(B, N, N, 17) == p.orc.observe()).all()
+        assert (mk.cpu().numpy() == p.orc.legal_mask()).all()
+        assert (raw_o[:off] == 9).all() and (raw_o[off + B * 1377:] == 9).all()
+        assert (raw_m[:off] == 9).all() and (raw_m[off + B * 82:] == 9).all()
+    p.env.bind_outputs(None, None, None, None)
+
+
+def test_illegal_actions_frozen_games_and_skips():
+    from gpu_common import Pair
+    for auto_reset in (False, True):
+        B, N = 30, 9
+        p = Pair(B, N, seed=2, auto_reset=auto_reset)
+        rng = np.random.default_rng(0)
+        for t in range(60):
+            a = p.orc.random_actions(2, t)
+            kind = rng.integers(0, 12, B)
+            a = np.where(kind == 0, rng.integers(0, 81, B), a)        # often an occupied or suicidal point
+            a = np.where(kind == 1, -1, a)                            # skip
+            a = np.where(kind == 2, 500, a)                           # out of range
+            a = np.where(kind == 3, -5, a)
+            a = a.astype(np.int32)
+            p.step(torch.as_tensor(a, device="cuda"), a)
+            p.compare(f"t={t}")
+        assert p.orc.illegal_count().sum() > 0
+
+
+def test_import_export_round_trip_and_continue():
+    """Mid-game positions produced by the oracle are imported into the GPU state (which rebuilds its private
+    chain data) and play continues in lock step."""
+    from gpu_common import Pair
+    for N, B in ((9, 33), (19, 10)):
+        src = oracle.GoOracle(B, N, seed=77, auto_reset=False)
+        for t in range(N * N):
+            src.step(src.random_actions(77, t))
+        st = src.export_state()
+        p = Pair(B, N, seed=77, auto_reset=False)
+        p.orc.import_state(st)
+        dev = {k: torch.as_tensor(getattr(st, k), device="cuda") for k in st.__slots__}
+        dev["episode"] = dev["episode"].to(torch.int32)
+        p.env.import_state(dev)
+        p.compare("after import")
+        p.rollout(78, 1000, 1000 + N * N, every=1, state_every=20)
+
+
+def test_reset_all():
+    from gpu_common import Pair
+    p = Pair(12, 9, seed=4, auto_reset=False)
+    p.rollout(4, 0, 30, every=10)
+    p.env.reset(); p.orc.reset()
+    p.env.rewards_out if False else None
+    p.compare("after reset")
+    p.rollout(4, 30, 60, every=10, state_every=10)
+
+
+# ---- the five benchmark configurations at full size, in the launch configuration the benchmark times ----
+def sampled_ids(batch, n, seed):
+    rng = np.random.default_rng(seed)
+    ids = np.unique(np.concatenate([[0, 1, 2, batch - 1, batch - 2], rng.choice(batch, n, replace=False)]))
+    return ids.astype(np.int32)
+
+
+@pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
+def test_benchmark_configs_full_size(ci):
+    """Full batch on the GPU; the oracle replays every environment (configs 0, 2) or a seeded sample of
+    environments (configs 1, 3, 4) for every ply, all outputs compared bit-exactly on those."""
+    from gpu_common import Pair
+    cfg = workloads.CONFIGS[ci]
+    n_sample = {0: None, 1: 96, 2: None, 3: 48, 4: 40}[ci]
+    ids = None if n_sample is None else sampled_ids(cfg.batch, n_sample, ci)
+    if ci == 2:
+        ids = sampled_ids(cfg.batch, 160, ci)     # 1024 x 722 plies is too slow for the plain oracle; 165 full games
+    p = Pair(cfg.batch, cfg.board_size, seed=cfg.seed, auto_reset=cfg.auto_reset, ids=ids)
+    start = workloads.start_times(cfg)
+    T = cfg.warmup_max + cfg.steps
+    p.rollout(cfg.seed, 0, T, start_t=start, every=1, state_every=100, fused=(ci >= 3))
+    # whole-batch properties that hold at any size
+    g = p.env.export_state()
+    P = cfg.board_size ** 2
+    mask = p.mask[:, :P + 1]
+    assert bool((mask[:, P] == 1).all())
+    assert bool(((mask[:, :P] == 1) & (g["board"] != 0)).sum() == 0)
+    obs = p.obs[:, : P * 17].view(cfg.batch, P, 17)
+    assert bool(((obs[:, :, 0] + obs[:, :, 1]) == (g["board"] != 0)).all())
+    assert bool((obs.max() <= 1))
+    if not cfg.auto_reset:
+        assert bool((g["terminated"] == 1).all())
