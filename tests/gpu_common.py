@@ -24,6 +24,8 @@ class Pair:
         self.orc = oracle.GoOracle(nb, N, seed=seed, komi_x2=komi_x2, max_steps=max_steps, auto_reset=auto_reset, env_ids=self.ids)
         self.sel = None if ids is None else torch.as_tensor(self.ids.astype(np.int64), device="cuda")
         self.bound = bind
+        self.n_compared = 0      # environment-plies whose outputs were compared
+        self.n_actions = 0
         if bind:
             self.mask = self.env.new_mask()
             self.obs = self.env.new_obs() if emit_obs else None
@@ -54,6 +56,7 @@ class Pair:
 
     def compare(self, tag="", state=True, obs=True):
         o = self.orc
+        self.n_compared += o.B
         assert (self.gpu_mask() == o.legal_mask()).all(), f"mask {tag}"
         if obs:
             assert (self.gpu_obs() == o.observe()).all(), f"obs {tag}"
@@ -77,6 +80,7 @@ class Pair:
         for t in range(t0, t1):
             a_c = self.orc.random_actions(seed, t, st_c)
             assert (self.pick(a_g) == a_c).all(), f"actions t={t}"
+            self.n_actions += int((a_c >= 0).sum())
             if fused and t + 1 < t1:
                 nxt = self.env.step_sample(a_g, seed, t + 1, st_g)
                 self.orc.step(a_c)

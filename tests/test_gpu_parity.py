@@ -65,6 +65,7 @@ def test_rollout_every_env_every_ply(N, B, T, auto_reset):
     from gpu_common import Pair
     p = Pair(B, N, seed=N + B, auto_reset=auto_reset)
     p.rollout(N + B, 0, T, every=1, state_every=25)
+    assert p.n_compared == B * T and p.n_actions == B * T
     s = p.orc.export_state()
     assert s.episode.max() >= 1 if auto_reset else (s.terminated == 1).all()
 
@@ -153,7 +154,6 @@ def test_reset_all():
     p = Pair(12, 9, seed=4, auto_reset=False)
     p.rollout(4, 0, 30, every=10)
     p.env.reset(); p.orc.reset()
-    p.env.rewards_out if False else None
     p.compare("after reset")
     p.rollout(4, 30, 60, every=10, state_every=10)
 
@@ -179,6 +179,10 @@ def test_benchmark_configs_full_size(ci):
     start = workloads.start_times(cfg)
     T = cfg.warmup_max + cfg.steps
     p.rollout(cfg.seed, 0, T, start_t=start, every=1, state_every=100, fused=(ci >= 3))
+    nb = p.orc.B
+    assert p.n_compared == nb * T
+    assert p.n_actions == (nb * T if start is None else int((T - start[ids]).sum()))
+    print(f"config {ci}: {cfg.batch} envs on the GPU, {nb} replayed by the oracle, {T} launches, {p.n_actions} plies compared")
     # whole-batch properties that hold at any size
     g = p.env.export_state()
     P = cfg.board_size ** 2
