@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched Go environment step on one MI355X.
+
+One "step" is one pass of the whole hot path over the batch: draw a uniform random legal action for every
+game, apply it (legality gate, placement, capture, ko, history, termination + area score, auto-reset), and
+emit the next legal mask [B][362], observation [B][19][19][17], rewards and terminated flags.  The default
+workload is the headline configuration: 19x19, 16384 games, seed 3, auto-reset, 2000 plies per game.
+
+Prints ONE JSON line (see README for the fields).  Inputs are synthetic by construction: the
+paper's own benchmark is random play from the empty board (Sec. 4.1).
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import threading
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
+
+
+def algorithmic_bytes_per_ply(N, with_obs):
+    """Bytes one ply must move whatever the implementation: action in, packed positions in/out, scalars,
+    legal mask and observation out.  19x19 with observation: 7272 B."""
+    P = N * N
+    packed = (P + 7) // 8                      # one colour of one position, bit-packed
+    total = 4                                  # action
+    total += (7 * 2 * packed) if with_obs else 2 * packed   # positions read (7 older ones feed the observation)
+    total += 24                                # per-game scalars read + written
+    total += 2 * packed                        # new position written
+    total += P + 1                             # legal mask bytes
+    total += P * 17 if with_obs else 0         # observation bytes
+    total += 9                                 # rewards[2] + terminated
+    return total
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel, taken from the committed rocprofv3 counter summary."""
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(cfg, steps, n_threads, envs_per_thread):
+    """The CPU oracle as it stands on the same workload: the first n_threads*envs_per_thread environments
+    of the configuration, all `steps` plies, sharded over host threads (the C calls release the GIL)."""
+    import numpy as np
+
+    import oracle
+
+    oracle.lib()
+    done = [0] * n_threads
+
+    def work(i):
+        ids = np.arange(i * envs_per_thread, (i + 1) * envs_per_thread, dtype=np.int32)
+        o = oracle.GoOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids)
+        for t in range(steps):
+            o.step(o.random_actions(cfg.seed, t))
+        done[i] = envs_per_thread * steps
+
+    def run(k):
+        th = [threading.Thread(target=work, args=(i,)) for i in range(k)]
+        t0 = time.perf_counter()
+        for x in th: x.start()
+        for x in th: x.join()
+        return sum(done[:k]) / (time.perf_counter() - t0)
+
+    single = run(1)
+    multi = run(n_threads) if n_threads > 1 else single
+    return single, multi
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--config", type=int, default=3, help="index into workloads.CONFIGS (3 = headline)")
+    ap.add_argument("--mode", choices=["fused", "separate"], default="fused",
+                    help="fused: the step kernel also draws the next action; separate: sampler kernel + step kernel")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-obs", action="store_true", help="do not emit the observation (not the headline metric)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (games are independent; more GPUs would shard the batch "
+              "with no communication); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2303_17503_amd as pg
+    from paper_2303_17503_amd import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = workloads.CONFIGS[args.config]
+    B, N, seed = cfg.batch, cfg.board_size, cfg.seed
+    K, Wm = args.steps, args.warmup
+    with_obs = not args.no_obs
+
+    env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
+    mask = env.new_mask()
+    obs = env.new_obs() if with_obs else None
+    rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
+    term = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    env.bind_outputs(mask, obs, rew, term)
+    start = workloads.start_times(cfg)
+    start_dev = None if start is None else torch.as_tensor(start, device="cuda")
+    acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
+    t_base = 0
+
+    def run_steps(t0, n, events=None):
+        """n passes of the hot path for launches t0..t0+n-1; acts[t & 1] holds the actions of launch t."""
+        for i in range(n):
+            t = t0 + i
+            if events is not None:
+                events[i][0].record()
+            if args.mode == "fused":
+                env.step_sample(acts[t & 1], seed, t + 1, start_dev, out=acts[(t + 1) & 1])
+            else:
+                env.step(acts[t & 1])
+            if events is not None:
+                events[i][1].record()
+            if args.mode != "fused":
+                env.random_actions(seed, t + 1, start_dev, out=acts[(t + 1) & 1])
+
+    # config 4: the warm-up plies that build the mid-game positions are not part of the measurement
+    pre = cfg.warmup_max
+    env.random_actions(seed, 0, start_dev, out=acts[0])
+    run_steps(0, pre + Wm)
+    t_base = pre + Wm
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(t_base, K)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_base += K
+
+    # per-launch duration of the step kernel: HIP events on the stream the kernels run on
+    n_ev = min(K, 500)
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    run_steps(t_base, n_ev, events)
+    torch.cuda.synchronize()
+    kern_ms = sum(a.elapsed_time(b) for a, b in events) / n_ev
+    t_base += n_ev
+
+    # a plain device copy of the same number of bytes as one step writes, as a practical ceiling
+    nbytes = B * (N * N * 17 + N * N + 1)
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5): dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(50): dst.copy_(src)
+    e1.record(); torch.cuda.synchronize()
+    copy_gbs = 2 * nbytes * 50 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    bytes_ply = algorithmic_bytes_per_ply(N, with_obs)
+    achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
+    kname = "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"go_step_kernel_{cfg.name}_pmc.txt")) if with_obs and args.mode == "fused" else None
+    out = {
+        "metric": "Go env steps/sec on 1 MI355X (19x19, batch 16384, random legal play); HBM GB/s % peak",
+        "value": B * K / wall,
+        "unit": "env steps/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": Wm,
+        "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "board_size": N, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset,
+                   "observation": with_obs, "mode": args.mode, "komi": cfg.komi_x2 / 2, "pre_warmup_plies_max": cfg.warmup_max},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
+                     "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
+    }
+    if not args.no_cpu_baseline:
+        n_threads = max(1, min(16, os.cpu_count() or 1))
+        envs_per_thread = 16
+        cpu_steps = min(K, 2000)
+        single, multi = cpu_baseline(cfg, cpu_steps, n_threads, envs_per_thread)
+        out["cpu_baseline"] = {"value": multi, "unit": "env steps/s", "cores": n_threads, "kind": "oracle",
+                               "sample": f"first {n_threads * envs_per_thread} environments of {cfg.name} (same seed and sampler), "
+                                         f"{cpu_steps} plies each, {envs_per_thread} per host thread; warm-up of config 4 not replayed",
+                               "single_core_value": single}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
