@@ -101,6 +101,20 @@ int pgxgo_random_actions(pgxgo_t h, uint32_t seed, uint32_t t, const int32_t* st
 int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev,
                       int32_t* next_actions_dev);
 
+/* `steps` plies of uniform random legal play in ONE kernel launch (Sec. 2: all-on-device loops in the style
+ * of the Anakin architecture; Sec. 4.1: random policy with auto-reset).  Exactly equivalent to
+ *   for i in 0..steps-1: pgxgo_random_actions(seed, t0+i, start_t_dev, a); pgxgo_step(a)
+ * but the game state stays in registers between plies and only outputs go to memory.  The outputs of ply i
+ * are written to slice (i mod slices) of the caller's trajectory buffers, each of which may be NULL:
+ *   actions_dev [slices][batch] int32 (the drawn action, -1 while an environment waits for its start time),
+ *   rewards_dev [slices][batch][2] float32, terminated_dev [slices][batch] uint8,
+ *   mask_dev [slices][batch][mask_pitch] uint8, obs_dev [slices][batch][obs_pitch] uint8,
+ * with the meanings of pgxgo_bind_outputs (the legal mask and observation are those AFTER the ply).
+ * slices = 1 overwrites one set of buffers every ply; slices = steps records the whole trajectory.
+ * Buffers bound with pgxgo_bind_outputs are not touched. */
+int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev,
+                  int32_t* actions_dev, float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev);
+
 /* Getters for the current state; each enqueues one kernel or copy into the caller's buffer. */
 int pgxgo_legal_mask(pgxgo_t h, uint8_t* dst_dev /* [batch][mask_pitch] */);
 int pgxgo_observe(pgxgo_t h, uint8_t* dst_dev /* [batch][obs_pitch] */);

@@ -5,7 +5,7 @@ import os
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libpgxgo.so")
+LIB_PATH = os.environ.get("PGXGO_LIB") or os.path.join(HERE, "libpgxgo.so")   # PGXGO_LIB: load another build of the same library
 
 _lib = None
 
@@ -37,6 +37,7 @@ def lib():
         L.pgxgo_step.argtypes = [vp, vp]
         L.pgxgo_random_actions.argtypes = [vp, u32, u32, vp, vp]
         L.pgxgo_step_sample.argtypes = [vp, vp, u32, u32, vp, vp]
+        L.pgxgo_rollout.argtypes = [vp, i32, i32, u32, u32, vp, vp, vp, vp, vp, vp]
         for n in ("legal_mask", "observe", "rewards", "terminated", "current_player"):
             getattr(L, "pgxgo_" + n).argtypes = [vp, vp]
         L.pgxgo_export_state.argtypes = [vp] * 11
@@ -145,6 +146,18 @@ class GoEnv:
         if start_t is not None: _need(start_t, torch.int32, (self.B,), "start_t")
         _check(lib().pgxgo_step_sample(self._h, _ptr(actions), seed & 0xFFFFFFFF, t & 0xFFFFFFFF, _ptr(start_t), _ptr(out)), "pgxgo_step_sample")
         return out
+
+    def rollout(self, steps, seed, t0, start_t=None, slices=1, actions=None, rewards=None, terminated=None, mask=None, obs=None):
+        """`steps` plies of random legal play in one launch; ply i writes slice i % slices of the given buffers."""
+        S = int(slices)
+        if actions is not None: _need(actions, torch.int32, (S, self.B), "actions")
+        if rewards is not None: _need(rewards, torch.float32, (S, self.B, 2), "rewards")
+        if terminated is not None: _need(terminated, torch.uint8, (S, self.B), "terminated")
+        if mask is not None: _need(mask, torch.uint8, (S, self.B, self.mask_pitch), "mask")
+        if obs is not None: _need(obs, torch.uint8, (S, self.B, self.obs_pitch), "obs")
+        if start_t is not None: _need(start_t, torch.int32, (self.B,), "start_t")
+        _check(lib().pgxgo_rollout(self._h, int(steps), S, seed & 0xFFFFFFFF, t0 & 0xFFFFFFFF, _ptr(start_t), _ptr(actions), _ptr(rewards),
+                                   _ptr(terminated), _ptr(mask), _ptr(obs)), "pgxgo_rollout")
 
     def legal_mask(self, out=None):
         out = self.new_mask() if out is None else _need(out, torch.uint8, (self.B, self.mask_pitch), "mask")

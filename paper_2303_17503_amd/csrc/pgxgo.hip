@@ -10,10 +10,14 @@
 //     lanes j*(N+1)+1 .. j*(N+1)+N, and lanes j*(N+1) stay all-zero "sentinel rows", so a one-lane DPP
 //     wave shift moves every row to its north/south neighbour and brings zeros in from off the board.
 //   * Stones are row bitboards (bit c = column c).  East/west neighbours are register shifts, north/south
-//     neighbours are DPP shifts; a flood-fill step is ~7 VALU instructions for all W boards at once.
+//     neighbours are DPP shifts; a flood-fill step is a handful of VALU instructions for all W boards at once.
+//   * Facts about a whole board (a move is legal, a chain has one liberty, ...) are kept as 64-bit lane
+//     masks in scalar registers: a ballot, a few scalar AND/popcount per board with compile-time segment
+//     masks, and the mask is used directly as the select condition of the next vector instruction.
 //   * The state keeps, besides the stones, the set of stones whose chain has exactly one liberty
 //     ("atari sets").  With them captures, the ko test and the whole legal mask are stencils; only the
-//     chains touched by the move are re-flooded (the merged chain and at most four opposing neighbours).
+//     chains touched by the move are re-flooded (the merged chain and at most four opposing neighbours),
+//     and a flood stops as soon as two liberties have been seen.
 //   * History is stored point-major: 16 bits per point = 8 plies x (black, white), two points per dword,
 //     so a ply is one shift-and-insert per dword and the [N][N][17] byte observation is produced by
 //     building the 17-bit-per-point bit stream of a board in LDS and expanding 16 bits -> 16 bytes per
@@ -39,6 +43,11 @@ thread_local int g_last_hip = 0;
     }                                                  \
   } while (0)
 
+#ifndef PGXGO_WAVES_PER_BLOCK
+#define PGXGO_WAVES_PER_BLOCK 4
+#endif
+constexpr int kWavesPerBlock = PGXGO_WAVES_PER_BLOCK;   // wavefronts never synchronise with each other; this only shapes the launch
+
 // ------------------------------------------------------------------------------------------------
 // geometry
 // ------------------------------------------------------------------------------------------------
@@ -49,8 +58,9 @@ struct Geo {
   static constexpr int STRIDE = N + 1;        // lanes per board, one of them the zero sentinel row
   static constexpr int W = 63 / STRIDE;       // boards per wavefront
   static constexpr int HD = (N + 1) / 2;      // history dwords per row, two points per dword
-  static constexpr int REC = HD + 6;          // + black, white, atari-black, atari-white, legal, spare
-  static constexpr int NQ = (REC + 3) / 4;    // 16-byte planes per row record
+  static constexpr int REC = HD + 4;          // + black, white, atari-black, atari-white
+  static constexpr int NQ = REC / 4;          // full 16-byte planes per row record
+  static constexpr int REM = REC % 4;         // dwords of the last, narrower plane
   static constexpr uint32_t FULL = (1u << N) - 1u;
   static constexpr int OBS = P * 17;          // observation bytes per board
   static constexpr int ROWBITS = N * 17;      // observation bits contributed by one row
@@ -58,6 +68,11 @@ struct Geo {
   static constexpr int NI = ROWBITS / 32 - 1;          // dwords 1..NI of the shifted string are never shared with another row
   static constexpr int OBS_DW = ((OBS + 15 + 31) / 32 + 3) / 4 * 4;   // LDS dwords of one board's bit stream (+ up to 15 lead bits)
   static constexpr int MASK_DW = ((A + 15 + 31) / 32 + 3) / 4 * 4;
+  static constexpr int OBS_ROUNDS = (OBS / 16 + 63) / 64;   // 64-lane rounds of 16-byte groups per board (whole groups <= OBS/16)
+  static constexpr int MASK_ROUNDS = (A / 16 + 63) / 64;
+  static constexpr size_t row_bytes = (size_t)REC * 4;
+  // lanes holding the rows of board slot j
+  static constexpr uint64_t seg(int j) { return ((1ull << N) - 1ull) << (j * STRIDE + 1); }
 };
 
 // per-board scalars, one 16-byte record per environment
@@ -105,14 +120,19 @@ __device__ __forceinline__ uint32_t from_lane_above(uint32_t x) {  // lane i rec
 // all 4-neighbours of the set x (bits beyond column N-1 may be set; callers intersect with on-board sets)
 __device__ __forceinline__ uint32_t dilate(uint32_t x) { return (x << 1) | (x >> 1) | from_lane_below(x) | from_lane_above(x); }
 
-__device__ __forceinline__ bool any_in_board(bool pred, uint64_t seg) { return (__ballot(pred) & seg) != 0ull; }
+// A fact about a whole board, known to every lane of the board: does `pred` hold in any of its rows?
+// (seglo/seghi = the lanes holding the rows of the calling lane's board)
+__device__ __forceinline__ bool board_any(bool pred, uint32_t seglo, uint32_t seghi) {
+  const uint64_t m = __ballot(pred);
+  return (((uint32_t)m & seglo) | ((uint32_t)(m >> 32) & seghi)) != 0u;
+}
 
-// number of set bits of a board-wide set given by its row words, saturated at 2
-__device__ __forceinline__ int count012(uint32_t w, uint64_t seg) {
-  uint64_t nz = __ballot(w != 0u) & seg;
-  uint64_t multi = __ballot((w & (w - 1u)) != 0u) & seg;
-  int c = __popcll(nz);
-  return (multi != 0ull || c >= 2) ? 2 : c;
+// Size class of a board-wide set given by its row words: exactly one element / two or more.
+__device__ __forceinline__ void board_count(uint32_t w, uint32_t seglo, uint32_t seghi, bool& one, bool& two) {
+  const uint64_t nz = __ballot(w != 0u), mu = __ballot((w & (w - 1u)) != 0u);
+  const int c = __popc((uint32_t)nz & seglo) + __popc((uint32_t)(nz >> 32) & seghi);
+  two = (((uint32_t)mu & seglo) | ((uint32_t)(mu >> 32) & seghi)) != 0u || c >= 2;
+  one = !two && c == 1;
 }
 
 // connected component(s) of `seed` inside S
@@ -127,28 +147,6 @@ __device__ __forceinline__ uint32_t flood_plain(uint32_t seed, uint32_t S) {
   return F;
 }
 
-// Chain of `seed` inside S and the class (0, 1, 2 = two or more) of its liberty count in E.
-// With EARLY the search of a board stops as soon as two liberties are known; F is then partial.
-template <bool EARLY>
-__device__ __forceinline__ void flood_libs(uint32_t seed, uint32_t S, uint32_t E, uint64_t seg, uint32_t& Fout, int& cls) {
-  uint32_t F = seed;
-  bool done = !any_in_board(seed != 0u, seg);
-  cls = 0;
-  for (;;) {
-    uint32_t D = dilate(F);
-    int c = count012(D & E, seg);
-    uint32_t G = F | (D & S);
-    bool chg = any_in_board(G != F, seg);
-    if (!done) {
-      if (EARLY && c == 2) { done = true; cls = 2; }
-      else if (!chg) { done = true; cls = c; }
-      else F = G;
-    }
-    if (__ballot(!done) == 0ull) break;
-  }
-  Fout = F;
-}
-
 // ------------------------------------------------------------------------------------------------
 // lane bookkeeping
 // ------------------------------------------------------------------------------------------------
@@ -157,18 +155,19 @@ struct Lane {
   int lane, j, r, b;     // lane id, board slot in the wavefront, row, global environment index
   bool valid;            // this lane holds a real row of a real board
   bool boardok;          // slot j holds a real board (also true for its sentinel lane)
-  uint64_t seg;          // lanes of the rows of this lane's board
+  uint32_t seglo, seghi; // lanes of the rows of this lane's board
   uint32_t full;         // FULL on valid lanes, else 0
-  __device__ __forceinline__ Lane(int wave, int B) {
+  __device__ __forceinline__ Lane(int wave, int lane_, int B) {
     using G = Geo<N>;
-    lane = threadIdx.x;
+    lane = lane_;
     j = lane / G::STRIDE;
     int rr = lane - j * G::STRIDE;
     r = rr - 1;
     b = wave * G::W + j;
     boardok = (j < G::W) && (b < B);
     valid = boardok && rr >= 1;
-    seg = (j < G::W) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
+    uint64_t seg = (j < G::W) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
+    seglo = (uint32_t)seg; seghi = (uint32_t)(seg >> 32);
     full = valid ? G::FULL : 0u;
   }
 };
@@ -176,41 +175,46 @@ struct Lane {
 template <int N>
 struct Row {                      // per-lane registers: one row of one board
   uint32_t h[Geo<N>::HD];         // history halfwords, bit 2i = black i plies ago, bit 2i+1 = white
-  uint32_t bk, wt, ab, aw, legal; // stones, atari sets, legal points of the player to move
+  uint32_t bk, wt, ab, aw;        // stones and atari sets (stones of chains with exactly one liberty)
 };
 
+// record dword k of row idx lives in plane k/4 (16-byte planes first, then one narrower plane)
 template <int N>
 __device__ __forceinline__ void load_row(const uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, Row<N>& R) {
   using G = Geo<N>;
-  uint32_t rec[G::NQ * 4];
+  uint32_t rec[G::NQ * 4 + 4];
 #pragma unroll
-  for (int k = 0; k < G::NQ * 4; ++k) rec[k] = 0u;
+  for (int k = 0; k < G::NQ * 4 + 4; ++k) rec[k] = 0u;
   if (L.valid) {
-    size_t idx = (size_t)L.b * N + L.r;
+    const size_t idx = (size_t)L.b * N + L.r;
 #pragma unroll
     for (int k = 0; k < G::NQ; ++k) {
       uint4 v = planes[(size_t)k * rows_total + idx];
       rec[4 * k] = v.x; rec[4 * k + 1] = v.y; rec[4 * k + 2] = v.z; rec[4 * k + 3] = v.w;
     }
+    const uint32_t* tail = (const uint32_t*)(planes + (size_t)G::NQ * rows_total);
+    if constexpr (G::REM == 2) { uint2 v = *(const uint2*)(tail + idx * 2); rec[4 * G::NQ] = v.x; rec[4 * G::NQ + 1] = v.y; }
+    if constexpr (G::REM == 1) { rec[4 * G::NQ] = tail[idx]; }
   }
 #pragma unroll
   for (int k = 0; k < G::HD; ++k) R.h[k] = rec[k];
-  R.bk = rec[G::HD]; R.wt = rec[G::HD + 1]; R.ab = rec[G::HD + 2]; R.aw = rec[G::HD + 3]; R.legal = rec[G::HD + 4];
+  R.bk = rec[G::HD]; R.wt = rec[G::HD + 1]; R.ab = rec[G::HD + 2]; R.aw = rec[G::HD + 3];
 }
 
 template <int N>
 __device__ __forceinline__ void store_row(uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, const Row<N>& R) {
   using G = Geo<N>;
-  uint32_t rec[G::NQ * 4];
-#pragma unroll
-  for (int k = 0; k < G::NQ * 4; ++k) rec[k] = 0u;
+  uint32_t rec[G::NQ * 4 + 4];
 #pragma unroll
   for (int k = 0; k < G::HD; ++k) rec[k] = R.h[k];
-  rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw; rec[G::HD + 4] = R.legal;
+  rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw;
   if (L.valid) {
-    size_t idx = (size_t)L.b * N + L.r;
+    const size_t idx = (size_t)L.b * N + L.r;
 #pragma unroll
     for (int k = 0; k < G::NQ; ++k) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
+    uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
+    if constexpr (G::REM == 2) *(uint2*)(tail + idx * 2) = make_uint2(rec[4 * G::NQ], rec[4 * G::NQ + 1]);
+    if constexpr (G::REM == 1) tail[idx] = rec[4 * G::NQ];
   }
 }
 
@@ -227,24 +231,47 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
   return E & ~kobit & dilate(support);
 }
 
+// LDS traffic between the lanes of one wavefront needs no hardware barrier (a wavefront's LDS operations
+// execute in program order); this only keeps the compiler from moving accesses across the hand-over.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ------------------------------------------------------------------------------------------------
 // bit stream -> byte stream.  `bits` (LDS) holds bit (head+i) = byte i of the destination, head = the
 // destination's offset from the previous 16-byte boundary.  Whole aligned 16-byte groups are written as
-// vectors, the ragged ends byte by byte.
+// vectors (ROUNDS rounds of 64 lanes cover them all), the ragged ends byte by byte.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
 
-__device__ __forceinline__ void emit_bytes(const uint32_t* bits, uint8_t* dst, uint32_t nbytes, int lane) {
+// 256-entry table in LDS: entry x = the eight bytes (0/1) of the bits of x.  Filled once per block.
+__device__ __forceinline__ void fill_spread_table(uint2* lut) {
+  for (uint32_t x = threadIdx.x; x < 256u; x += blockDim.x) lut[x] = make_uint2(spread4(x & 15u), spread4(x >> 4));
+  __syncthreads();
+}
+
+template <int NBYTES, int ROUNDS>
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, int lane) {
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
   uint8_t* base = dst - head;
-  const uint32_t total = head + nbytes;
-  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;
+  const uint32_t total = head + NBYTES;
+  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1; m1 - m0 <= NBYTES/16 <= 64*ROUNDS
   const uint16_t* b16 = (const uint16_t*)bits;
-  for (uint32_t m = m0 + lane; m < m1; m += 64u) {
-    uint32_t v = b16[m];
-    uint4 o;
-    o.x = spread4(v & 15u); o.y = spread4((v >> 4) & 15u); o.z = spread4((v >> 8) & 15u); o.w = spread4((v >> 12) & 15u);
-    *(uint4*)(base + 16u * m) = o;
+  uint32_t v[ROUNDS];
+#pragma unroll
+  for (int i = 0; i < ROUNDS; ++i) {
+    const uint32_t m = m0 + 64u * i + lane;
+    v[i] = (i + 1 < ROUNDS || m < m1) ? b16[m] : 0u;
+  }
+#pragma unroll
+  for (int i = 0; i < ROUNDS; ++i) {
+    const uint32_t m = m0 + 64u * i + lane;
+    const uint2 lo = lut[v[i] & 255u], hi = lut[v[i] >> 8];
+    if (i + 1 < ROUNDS || m < m1) {
+      *(uint4*)(base + 16u * m) = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
   }
   if (lane < 32) {
     uint32_t i = lane & 15u, pos;
@@ -257,26 +284,27 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, uint8_t* dst, u
 
 // Legal mask bytes [N*N+1] and observation bytes [N][N][17] of every board of the wavefront.
 template <int N>
-__device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, int wtm, int wave, int B,
+__device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
-                                             uint32_t* lds_mask, uint32_t* lds_obs) {
+                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut) {
   using G = Geo<N>;
   if (mask) {
-    for (int i = L.lane; i < G::W * G::MASK_DW; i += 64) lds_mask[i] = 0u;
-    __syncthreads();
+    if (L.lane < G::W * G::MASK_DW) lds_mask[L.lane] = 0u;
+    static_assert(G::W * G::MASK_DW <= 64, "mask staging is cleared by one store per lane");
+    wave_lds_fence();
     if (L.valid) {
       uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u);
       uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
       uint32_t* reg = lds_mask + L.j * G::MASK_DW;
-      atomicOr(&reg[q], R.legal << s);
-      if (s + N > 32u) atomicOr(&reg[q + 1], R.legal >> (32u - s));
+      atomicOr(&reg[q], legal << s);
+      if (s + N > 32u) atomicOr(&reg[q + 1], legal >> (32u - s));
       if (L.r == 0) { uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
     }
-    __syncthreads();
+    wave_lds_fence();
+#pragma unroll
     for (int jj = 0; jj < G::W; ++jj) {
-      int bb = wave * G::W + jj;
-      if (bb >= B) break;
-      emit_bytes(lds_mask + jj * G::MASK_DW, mask + (int64_t)bb * mask_pitch, G::A, L.lane);
+      const int bb = wave * G::W + jj;
+      if (bb < B) emit_bytes<G::A, G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)bb * mask_pitch, L.lane);
     }
   }
   if (obs) {
@@ -301,9 +329,12 @@ __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, 
     }
     {
       uint4* z = (uint4*)lds_obs;
-      for (int i = L.lane; i < G::W * G::OBS_DW / 4; i += 64) z[i] = make_uint4(0u, 0u, 0u, 0u);
+      constexpr int NZ = G::W * G::OBS_DW / 4;
+#pragma unroll
+      for (int i = 0; i < (NZ + 63) / 64; ++i)
+        if (i * 64 + 63 < NZ || i * 64 + L.lane < NZ) z[i * 64 + L.lane] = make_uint4(0u, 0u, 0u, 0u);
     }
-    __syncthreads();
+    wave_lds_fence();
     if (L.valid) {
       uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u);
       uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
@@ -318,92 +349,88 @@ __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, 
         else if (t) atomicOr(&reg[i], t);
       }
     }
-    __syncthreads();
+    wave_lds_fence();
+#pragma unroll
     for (int jj = 0; jj < G::W; ++jj) {
-      int bb = wave * G::W + jj;
-      if (bb >= B) break;
-      emit_bytes(lds_obs + jj * G::OBS_DW, obs + (int64_t)bb * obs_pitch, G::OBS, L.lane);
+      const int bb = wave * G::W + jj;
+      if (bb < B) emit_bytes<G::OBS, G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)bb * obs_pitch, L.lane);
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// the step kernel
+// uniform random legal action: the k-th legal action in ascending order, k = hash mod legal_count
 // ------------------------------------------------------------------------------------------------
-struct StepArgs {
-  uint4* planes;
-  uint4* meta;
-  const int32_t* actions;
-  float* rew;
-  uint8_t* term;
-  uint8_t* mask;
-  uint8_t* obs;
-  int64_t mask_pitch, obs_pitch;
-  int B;
-  uint32_t seed;
-  int komi_x2, max_steps, auto_reset;
-  // fused sampler
-  uint32_t sample_seed, sample_t;
-  const int32_t* start_t;
-  int32_t* next_actions;
+template <int N>
+struct Draw {          // the drawn action as every lane of the board sees it
+  bool pass, point;    // neither = the environment is still waiting for its start time (action -1)
+  int pr, pc;          // row and column when `point`
+  __device__ __forceinline__ int action() const { return pass ? Geo<N>::P : point ? pr * N + pc : -1; }
 };
 
 template <int N>
-__device__ __forceinline__ void sample_action(const Lane<N>& L, uint32_t legal, uint32_t seed, uint32_t t, const int32_t* start_t,
-                                              int32_t* out, int* lds_tmp) {
+__device__ __forceinline__ Draw<N> draw_action(const Lane<N>& L, uint32_t legal, uint32_t seed, uint32_t t, bool wait) {
   using G = Geo<N>;
-  int cnt = __popc(legal);
-  __syncthreads();
-  lds_tmp[L.lane] = cnt;
-  __syncthreads();
-  int before = 0, total = 1;   // pass is always legal
-  if (L.valid) {
-    for (int i = 0; i < N; ++i) {
-      int v = lds_tmp[L.j * G::STRIDE + 1 + i];
-      total += v;
-      if (i < L.r) before += v;
-    }
-    bool wait = start_t && (int64_t)t < (int64_t)start_t[L.b];
-    int k = (int)(env_hash(seed, 0u, (uint32_t)L.b, t) % (uint32_t)total);
-    if (wait) { if (L.r == 0) out[L.b] = -1; }
-    else if (k == total - 1) { if (L.r == 0) out[L.b] = G::P; }
-    else if (k >= before && k < before + cnt) {
-      uint32_t w = legal;
-      for (int i = k - before; i > 0; --i) w &= w - 1u;
-      out[L.b] = L.r * N + (__ffs(w) - 1);
-    }
+  const uint32_t cnt = __popc(legal);
+  // legal points in the rows above this one, and on the whole board, from ballots of the bits of cnt
+  uint32_t before = 0u, total = 1u;   // pass is always legal
+#pragma unroll
+  for (int k = 0; (1 << k) <= N; ++k) {
+    const uint64_t m = __ballot((cnt >> k) & 1u);
+    const uint32_t lo = (uint32_t)m & L.seglo, hi = (uint32_t)(m >> 32) & L.seghi;
+    before += __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u)) << k;
+    total += (uint32_t)(__popc(lo) + __popc(hi)) << k;
   }
+  const uint32_t k = env_hash(seed, 0u, (uint32_t)L.b, t) % total;
+  // position of the (n+1)-th set bit of the row word by halving (meaningful in the row that holds it)
+  uint32_t n = k - before, w = legal, pos = 0u;
+#pragma unroll
+  for (int width = 16; width >= 1; width >>= 1) {
+    const uint32_t c = __popc(w & ((1u << width) - 1u));
+    if (n >= c) { n -= c; w >>= width; pos += width; }
+  }
+  const bool mine = L.valid && k >= before && k < before + cnt;
+  const uint64_t sel = __ballot(mine);
+  const uint32_t slo = (uint32_t)sel & L.seglo, shi = (uint32_t)(sel >> 32) & L.seghi;
+  const int src = slo ? __ffs(slo) - 1 : 31 + __ffs(shi);   // lane of the chosen row (any lane when pass is drawn)
+  Draw<N> d;
+  d.pass = !wait && k == total - 1u;
+  d.point = !wait && k != total - 1u;
+  d.pr = (src & 63) - (L.j * G::STRIDE + 1);
+  d.pc = (int)__shfl((int)pos, src & 63);
+  return d;
 }
 
-template <int N, bool SAMPLE>
-__global__ void __launch_bounds__(64) go_step_kernel(StepArgs a) {
+// ------------------------------------------------------------------------------------------------
+// one ply for every board of the wavefront (steps a2-a8); registers in, registers out
+// ------------------------------------------------------------------------------------------------
+struct Rules {
+  uint32_t seed;
+  int komi_x2, max_steps, auto_reset;
+};
+
+// skip: leave the board alone.  want_pass / want_point(pr,pc): the requested action; anything else is illegal.
+// GATE: check the point against the mover's legal set (not needed for actions drawn from that set).
+// Out: rewards by player id, `flag` = the terminated output (game ended in this ply, or had ended before).
+template <int N, bool GATE>
+__device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, bool skip, bool want_pass, bool want_point,
+                                          int pr_in, int pc_in, float& rew0, float& rew1, bool& flag) {
   using G = Geo<N>;
-  __shared__ __attribute__((aligned(16))) uint32_t lds_obs[G::W * G::OBS_DW];
-  __shared__ __attribute__((aligned(16))) uint32_t lds_mask[G::W * G::MASK_DW];
-  __shared__ int lds_tmp[64];
-  const int wave = blockIdx.x;
-  const Lane<N> L(wave, a.B);
-  const size_t rows_total = (size_t)a.B * N;
-
-  Row<N> R;
-  load_row<N>(a.planes, rows_total, L, R);
-  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
-  const int act = L.boardok ? a.actions[L.b] : -1;
-
-  // ---- a1/a2: decode the action and gate it with the mover's legal mask --------------------------------
-  const bool skip = !L.boardok || act == -1;
   const bool frozen = !skip && m.term;
   const bool live = !skip && !frozen;
-  const bool is_pass = live && act == G::P;
-  const bool on_board = live && act >= 0 && act < G::P;
-  int pr = on_board ? act / N : -100, pc = on_board ? act - (act / N) * N : 0;
+  const bool is_pass = live && want_pass;
+  const bool on_board = live && want_point;
+  int pr = on_board ? pr_in : -100, pc = on_board ? pc_in : 0;
   uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
-  const bool playing = on_board && any_in_board((R.legal & pbit) != 0u, L.seg);
+  bool playing = on_board;
+  if (GATE) {
+    const uint32_t legal_now = legal_row<N>(L, R, m.wtm, m.ko);
+    playing = on_board && board_any((legal_now & pbit) != 0u, L.seglo, L.seghi);
+  }
   const bool illegal = live && !is_pass && !playing;
   if (!playing) { pr = -100; pbit = 0u; }
   const int wtm0 = m.wtm;
-
-  float rew0 = 0.f, rew1 = 0.f;
+  rew0 = 0.f; rew1 = 0.f;
 
   // ---- a3-a5: place the stone, capture, update the atari sets, ko ----------------------------------------
   if (__ballot(playing) != 0ull) {
@@ -414,39 +441,64 @@ __global__ void __launch_bounds__(64) go_step_kernel(StepArgs a) {
     const uint32_t nbW = (L.valid && L.r == pr) ? ((1u << pc) >> 1) : 0u;
     const uint32_t nbE = (L.valid && L.r == pr) ? ((2u << pc) & G::FULL) : 0u;
     const uint32_t nb = nbN | nbS | nbW | nbE;
+    const uint32_t friends = nb & own;   // own stones next to the new one
     own |= pbit;
     // opposing chains in atari that touch the new stone lose their last liberty
-    uint32_t cap = 0u;
+    int ko_new = -1;
     const uint32_t capseed = nb & aopp;
     if (__ballot(capseed != 0u) != 0ull) {
-      cap = flood_plain(capseed, aopp);
+      const uint32_t cap = flood_plain(capseed, aopp);
       opp &= ~cap; aopp &= ~cap;
       // own chains in atari next to the vacated points gain a liberty
-      uint32_t un = flood_plain(aown & dilate(cap), aown);
+      const uint32_t un = flood_plain(aown & dilate(cap), aown);
       aown &= ~un;
+      // simple ko: exactly one stone taken by a stone without friends whose only liberty is the vacated point
+      bool cap1, cap2, lib1, lib2;
+      board_count(cap, L.seglo, L.seghi, cap1, cap2);
+      board_count(nb & L.full & ~(own | opp), L.seglo, L.seghi, lib1, lib2);
+      const bool lone = !board_any(friends != 0u, L.seglo, L.seghi);
+      const bool cN = board_any((cap & nbN) != 0u, L.seglo, L.seghi), cS = board_any((cap & nbS) != 0u, L.seglo, L.seghi);
+      const bool cW = board_any((cap & nbW) != 0u, L.seglo, L.seghi);
+      const int p = pr * N + pc;
+      if (cap1 && lib1 && lone) ko_new = cN ? p - N : cS ? p + N : cW ? p - 1 : p + 1;
     }
     const uint32_t E = L.full & ~(own | opp);
-    // the chain of the new stone
-    uint32_t M; int clsM;
-    flood_libs<false>(pbit, own, E, L.seg, M, clsM);
-    aown = (aown & ~M) | (clsM == 1 ? M : 0u);
-    // opposing neighbour chains that survive have lost the liberty just filled
-    const uint32_t seeds[4] = {nbN & opp, nbS & opp, nbW & opp, nbE & opp};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      if (__ballot(seeds[d] != 0u) != 0ull) {
-        uint32_t F; int cls;
-        flood_libs<true>(seeds[d], opp, E, L.seg, F, cls);
-        if (cls == 1) aopp |= F;
-      }
+    // own chains in atari that the new stone joins stop being chains of their own
+    const uint32_t clrseed = friends & aown;
+    if (__ballot(clrseed != 0u) != 0ull) aown &= ~flood_plain(clrseed, aown);
+    // Liberty class of the new stone's chain (flood 0, through own stones) and of the surviving opposing
+    // neighbour chains, which lost the liberty just filled (floods 1-4, through opposing stones).  A flood
+    // leaves the race as soon as two liberties are known; one that converges with a single liberty has
+    // found a whole chain in atari.
+    uint32_t F0 = pbit, F1 = nbN & opp, F2 = nbS & opp, F3 = nbW & opp, F4 = nbE & opp;
+    bool run0 = board_any(F0 != 0u, L.seglo, L.seghi), run1 = board_any(F1 != 0u, L.seglo, L.seghi);
+    bool run2 = board_any(F2 != 0u, L.seglo, L.seghi), run3 = board_any(F3 != 0u, L.seglo, L.seghi);
+    bool run4 = board_any(F4 != 0u, L.seglo, L.seghi);
+    bool at0 = false, at1 = false, at2 = false, at3 = false, at4 = false;
+    auto flood_step = [&](uint32_t& F, uint32_t S, bool& run, bool& at) {
+      const uint32_t D = dilate(F);
+      const uint32_t Gn = F | (D & S);
+      bool one, two;
+      board_count(D & E, L.seglo, L.seghi, one, two);
+      const bool grew = board_any(Gn != F, L.seglo, L.seghi);
+      const bool conv = run && !two && !grew;
+      at = at || (conv && one);
+      run = run && !two && !conv;
+      F = Gn;
+    };
+    for (;;) {
+      const uint64_t r0 = __ballot(run0), r1 = __ballot(run1), r2 = __ballot(run2), r3 = __ballot(run3), r4 = __ballot(run4);
+      if ((r0 | r1 | r2 | r3 | r4) == 0ull) break;
+      if (r0 != 0ull) flood_step(F0, own, run0, at0);
+      if (r1 != 0ull) flood_step(F1, opp, run1, at1);
+      if (r2 != 0ull) flood_step(F2, opp, run2, at2);
+      if (r3 != 0ull) flood_step(F3, opp, run3, at3);
+      if (r4 != 0ull) flood_step(F4, opp, run4, at4);
     }
-    // simple ko: one stone taken by a lone stone that is left with a single liberty
-    const int ncap = count012(cap, L.seg), nM = count012(M, L.seg);
-    const bool capN = any_in_board((cap & nbN) != 0u, L.seg), capS = any_in_board((cap & nbS) != 0u, L.seg);
-    const bool capW = any_in_board((cap & nbW) != 0u, L.seg);
+    aown |= at0 ? F0 : 0u;
+    aopp |= (at1 ? F1 : 0u) | (at2 ? F2 : 0u) | (at3 ? F3 : 0u) | (at4 ? F4 : 0u);
     if (playing) {
-      const int p = pr * N + pc;
-      m.ko = (ncap == 1 && nM == 1 && clsM == 1) ? (capN ? p - N : capS ? p + N : capW ? p - 1 : p + 1) : -1;
+      m.ko = ko_new;
       R.bk = wtm0 ? opp : own; R.wt = wtm0 ? own : opp;
       R.ab = wtm0 ? aopp : aown; R.aw = wtm0 ? aown : aopp;
     }
@@ -457,30 +509,35 @@ __global__ void __launch_bounds__(64) go_step_kernel(StepArgs a) {
   if (moved) {
     m.steps += 1;
     m.wtm ^= 1;
-    // ---- a6: history push -------------------------------------------------------------------------------
+  }
+  // ---- a6: history push: every halfword shifts by one ply and takes the new position in its low bits -----
+  {
+    const uint32_t lo = (R.bk & 0x55555555u) | ((R.wt & 0x55555555u) << 1);   // bit 2j / 2j+1: black / white at column 2j
+    const uint32_t hi = ((R.bk >> 1) & 0x55555555u) | (R.wt & 0xAAAAAAAAu);   // the same for column 2j+1
 #pragma unroll
     for (int jd = 0; jd < G::HD; ++jd) {
-      uint32_t t = R.bk >> (2 * jd), u = R.wt >> (2 * jd);
-      uint32_t cur = (t & 1u) | ((u & 1u) << 1) | ((t & 2u) << 15) | ((u & 2u) << 16);
-      R.h[jd] = ((R.h[jd] << 2) & 0xFFFCFFFCu) | cur;
+      const uint32_t cur = ((lo >> (2 * jd)) & 3u) | (((hi >> (2 * jd)) & 3u) << 16);
+      const uint32_t pushed = ((R.h[jd] << 2) & 0xFFFCFFFCu) | cur;
+      R.h[jd] = moved ? pushed : R.h[jd];
     }
   }
 
   // ---- a7: termination and Tromp-Taylor area score ------------------------------------------------------
-  const bool score = moved && (m.passes >= 2 || m.steps >= a.max_steps);
+  const bool score = moved && (m.passes >= 2 || m.steps >= cfg.max_steps);
   if (__ballot(score) != 0ull) {
     const uint32_t E = L.full & ~(R.bk | R.wt);
     const uint32_t rb = flood_plain(E & dilate(R.bk), E);
     const uint32_t rw = flood_plain(E & dilate(R.wt), E);
-    int diff = __popc(R.bk | (rb & ~rw)) - __popc(R.wt | (rw & ~rb));
-    __syncthreads();
-    lds_tmp[L.lane] = diff;
-    __syncthreads();
-    int sum = 0;
-    if (L.valid)
-      for (int i = 0; i < N; ++i) sum += lds_tmp[L.j * G::STRIDE + 1 + i];
+    // per-board sum of (black area - white area) of the rows, from ballots of the bits of a biased row value
+    const uint32_t v = (uint32_t)(__popc(R.bk | (rb & ~rw)) - __popc(R.wt | (rw & ~rb)) + N);   // 0 .. 2N
+    int sum = -N * N;
+#pragma unroll
+    for (int k = 0; (1 << k) <= 2 * N; ++k) {
+      const uint64_t mk = __ballot((v >> k) & 1u);
+      sum += (__popc((uint32_t)mk & L.seglo) + __popc((uint32_t)(mk >> 32) & L.seghi)) << k;
+    }
     if (score) {
-      int d = 2 * sum - a.komi_x2;   // komi counts for White
+      int d = 2 * sum - cfg.komi_x2;   // komi counts for White
       float s = d > 0 ? 1.f : (d < 0 ? -1.f : 0.f);
       rew0 = m.bp == 0 ? s : -s;
       rew1 = -rew0;
@@ -496,47 +553,200 @@ __global__ void __launch_bounds__(64) go_step_kernel(StepArgs a) {
   if (ended) {
     m.term = 1;
     // ---- a8: auto-reset (Sec. 4.1) -------------------------------------------------------------------------
-    if (a.auto_reset) {
+    if (cfg.auto_reset) {
 #pragma unroll
       for (int jd = 0; jd < G::HD; ++jd) R.h[jd] = 0u;
       R.bk = R.wt = R.ab = R.aw = 0u;
       m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
       m.episode += 1;
-      m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
+      m.bp = (int)(env_hash(cfg.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
     }
   }
+  flag = ended || frozen;
+}
+
+// ------------------------------------------------------------------------------------------------
+// the step kernel: one launch = one ply of every environment
+// ------------------------------------------------------------------------------------------------
+struct StepArgs {
+  uint4* planes;
+  uint4* meta;
+  const int32_t* actions;
+  float* rew;
+  uint8_t* term;
+  uint8_t* mask;
+  uint8_t* obs;
+  int64_t mask_pitch, obs_pitch;
+  int B;
+  Rules rules;
+  // fused sampler
+  uint32_t sample_seed, sample_t;
+  const int32_t* start_t;
+  int32_t* next_actions;
+};
+
+template <int N, bool SAMPLE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
+  __shared__ uint2 lut[256];
+  fill_spread_table(lut);
+  const int wib = threadIdx.x >> 6;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  if (wave * G::W >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
+  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  const size_t rows_total = (size_t)a.B * N;
+
+  Row<N> R;
+  load_row<N>(a.planes, rows_total, L, R);
+  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  const int act = L.boardok ? a.actions[L.b] : -1;
+
+  // a1: decode the action
+  const bool skip = !L.boardok || act == -1;
+  const bool in_range = act >= 0 && act < G::P;
+  const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
+  float rew0, rew1;
+  bool flag;
+  step_core<N, true>(L, R, m, a.rules, skip, act == G::P, in_range, pr, pc, rew0, rew1, flag);
   if (!skip && L.valid && L.r == 0) {
-    a.rew[2 * (size_t)L.b] = rew0; a.rew[2 * (size_t)L.b + 1] = rew1;
-    a.term[L.b] = (uint8_t)((ended || frozen) ? 1 : 0);
+    *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
+    a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
 
   // ---- a9/a10: legal mask and observation of the player now to move --------------------------------------
-  R.legal = legal_row<N>(L, R, m.wtm, m.ko);
-  emit_outputs<N>(L, R, m.wtm, wave, a.B, a.mask, a.mask_pitch, a.obs, a.obs_pitch, lds_mask, lds_obs);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  emit_outputs<N>(L, R, legal, m.wtm, wave, a.B, a.mask, a.mask_pitch, a.obs, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
     store_row<N>(a.planes, rows_total, L, R);
     if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
   }
-  if (SAMPLE) sample_action<N>(L, R.legal, a.sample_seed, a.sample_t, a.start_t, a.next_actions, lds_tmp);
+  if (SAMPLE) {
+    const bool wait = L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
+    const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
+    if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// the rollout kernel: one launch = `steps` plies of uniform random legal play of every environment.  The
+// state stays in registers between plies; each ply's outputs go to slice (i mod slices) of the caller's
+// trajectory buffers.
+// ------------------------------------------------------------------------------------------------
+struct RolloutArgs {
+  uint4* planes;
+  uint4* meta;
+  int B;
+  Rules rules;
+  int steps, slices;
+  uint32_t seed, t0;
+  const int32_t* start_t;
+  int32_t* actions;     // [slices][B] or null
+  float* rew;           // [slices][B][2] or null
+  uint8_t* term;        // [slices][B] or null
+  uint8_t* mask;        // [slices][B][mask_pitch] or null
+  uint8_t* obs;         // [slices][B][obs_pitch] or null
+  int64_t mask_pitch, obs_pitch;
+};
+
+template <int N>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(RolloutArgs a) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
+  __shared__ uint2 lut[256];
+  fill_spread_table(lut);
+  const int wib = threadIdx.x >> 6;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  if (wave * G::W >= a.B) return;
+  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  const size_t rows_total = (size_t)a.B * N;
+
+  Row<N> R;
+  load_row<N>(a.planes, rows_total, L, R);
+  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  const int64_t start = (L.boardok && a.start_t) ? (int64_t)a.start_t[L.b] : INT64_MIN;
+  uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  int slice = 0;
+  for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
+    const uint32_t t = a.t0 + (uint32_t)i;
+    const bool wait = (int64_t)t < start;
+    const Draw<N> d = draw_action<N>(L, legal, a.seed, t, wait);
+    const bool skip = !L.boardok || wait;
+    float rew0, rew1;
+    bool flag;
+    step_core<N, false>(L, R, m, a.rules, skip, d.pass, d.point, d.pr, d.pc, rew0, rew1, flag);
+    legal = legal_row<N>(L, R, m.wtm, m.ko);
+    const size_t sb = (size_t)slice * a.B;
+    if (L.valid && L.r == 0) {
+      const size_t e = sb + L.b;
+      if (a.actions) a.actions[e] = d.action();
+      // a waiting environment reports the values a skipped step call leaves behind at the start: zeros
+      if (a.rew) *(float2*)(a.rew + 2 * e) = skip ? make_float2(0.f, 0.f) : make_float2(rew0, rew1);
+      if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
+    }
+    emit_outputs<N>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
+                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
+    wave_lds_fence();
+    slice = slice + 1 == a.slices ? 0 : slice + 1;
+  }
+  store_row<N>(a.planes, rows_total, L, R);
+  if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
 }
 
 // ------------------------------------------------------------------------------------------------
 // auxiliary kernels
 // ------------------------------------------------------------------------------------------------
 template <int N>
-__global__ void __launch_bounds__(64) go_emit_kernel(const uint4* planes, const uint4* meta, int B, uint8_t* mask, int64_t mask_pitch,
-                                                     uint8_t* obs, int64_t obs_pitch) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint4* planes, const uint4* meta, int B, uint8_t* mask,
+                                                                      int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch) {
   using G = Geo<N>;
-  __shared__ __attribute__((aligned(16))) uint32_t lds_obs[G::W * G::OBS_DW];
-  __shared__ __attribute__((aligned(16))) uint32_t lds_mask[G::W * G::MASK_DW];
-  const int wave = blockIdx.x;
-  const Lane<N> L(wave, B);
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
+  __shared__ uint2 lut[256];
+  fill_spread_table(lut);
+  const int wib = threadIdx.x >> 6;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  if (wave * G::W >= B) return;
+  const Lane<N> L(wave, threadIdx.x & 63, B);
   Row<N> R;
   load_row<N>(planes, (size_t)B * N, L, R);
   Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
-  emit_outputs<N>(L, R, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask, lds_obs);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  emit_outputs<N>(L, R, legal, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
+}
+
+// k-th legal action of the current position, same row-per-lane mapping as the step kernel
+template <int N>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(const uint4* planes, const uint4* meta, int B, uint32_t seed,
+                                                                                uint32_t t, const int32_t* start_t, int32_t* actions) {
+  using G = Geo<N>;
+  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  if (wave * G::W >= B) return;
+  const Lane<N> L(wave, threadIdx.x & 63, B);
+  Row<N> R;
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) R.h[k] = 0u;
+  R.bk = R.wt = R.ab = R.aw = 0u;
+  if (L.valid) {   // stones and atari sets are the last four dwords of the row record
+    const size_t idx = (size_t)L.b * N + L.r, rows_total = (size_t)B * N;
+    uint32_t rec[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int k = G::HD + i;
+      if (k < 4 * G::NQ) rec[i] = ((const uint32_t*)(planes + (size_t)(k / 4) * rows_total + idx))[k & 3];
+      else rec[i] = ((const uint32_t*)(planes + (size_t)G::NQ * rows_total))[idx * G::REM + (k - 4 * G::NQ)];
+    }
+    R.bk = rec[0]; R.wt = rec[1]; R.ab = rec[2]; R.aw = rec[3];
+  }
+  Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  const bool wait = L.boardok && start_t && (int64_t)t < (int64_t)start_t[L.b];
+  const Draw<N> d = draw_action<N>(L, legal, seed, t, wait);
+  if (L.valid && L.r == 0) actions[L.b] = d.action();
 }
 
 // new episode for every environment: empty board, Black to move, seat from the hash
@@ -547,11 +757,10 @@ __global__ void go_reset_kernel(uint4* planes, uint4* meta, float* rew, uint8_t*
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < rows_total) {
 #pragma unroll
-    for (int k = 0; k < G::NQ; ++k) {
-      uint32_t rec[4] = {0u, 0u, 0u, 0u};
-      if (G::HD + 4 >= 4 * k && G::HD + 4 < 4 * k + 4) rec[G::HD + 4 - 4 * k] = G::FULL;   // every point is legal
-      planes[(size_t)k * rows_total + i] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
-    }
+    for (int k = 0; k < G::NQ; ++k) planes[(size_t)k * rows_total + i] = make_uint4(0u, 0u, 0u, 0u);
+    uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
+#pragma unroll
+    for (int k = 0; k < G::REM; ++k) tail[i * G::REM + k] = 0u;
   }
   if (i < (size_t)B) {
     Meta m;
@@ -562,36 +771,6 @@ __global__ void go_reset_kernel(uint4* planes, uint4* meta, float* rew, uint8_t*
     meta[i] = pack_meta(m);
     rew[2 * i] = 0.f; rew[2 * i + 1] = 0.f; term[i] = 0;
   }
-}
-
-// k-th legal action of the stored legal words, one thread per environment
-template <int N>
-__global__ void go_random_actions_kernel(const uint4* planes, int B, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* actions) {
-  using G = Geo<N>;
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  if (start_t && (int64_t)t < (int64_t)start_t[b]) { actions[b] = -1; return; }
-  constexpr int slot = G::HD + 4;
-  const uint32_t* words = (const uint32_t*)(planes + (size_t)(slot / 4) * ((size_t)B * N) + (size_t)b * N) + (slot & 3);
-  uint32_t w[N];
-  int total = 1;
-#pragma unroll
-  for (int r = 0; r < N; ++r) { w[r] = words[4 * r]; total += __popc(w[r]); }
-  int k = (int)(env_hash(seed, 0u, (uint32_t)b, t) % (uint32_t)total);
-  int pick = G::P;
-#pragma unroll
-  for (int r = 0; r < N; ++r) {
-    int c = __popc(w[r]);
-    if (pick == G::P && k >= 0) {
-      if (k < c) {
-        uint32_t x = w[r];
-        for (int i = k; i > 0; --i) x &= x - 1u;
-        pick = r * N + (__ffs(x) - 1);
-        k = -1;
-      } else k -= c;
-    }
-  }
-  actions[b] = pick;
 }
 
 template <int N>
@@ -610,7 +789,7 @@ struct CanonArgs {
 template <int N>
 __global__ void __launch_bounds__(64) go_export_kernel(const uint4* planes, const uint4* meta, int B, CanonArgs c) {
   using G = Geo<N>;
-  const Lane<N> L(blockIdx.x, B);
+  const Lane<N> L(blockIdx.x, threadIdx.x, B);
   Row<N> R;
   load_row<N>(planes, (size_t)B * N, L, R);
   if (!L.valid) return;
@@ -641,11 +820,11 @@ __global__ void __launch_bounds__(64) go_export_kernel(const uint4* planes, cons
 template <int N>
 __global__ void __launch_bounds__(64) go_import_kernel(uint4* planes, uint4* meta, float* rew, uint8_t* term, int B, CanonArgs c) {
   using G = Geo<N>;
-  const Lane<N> L(blockIdx.x, B);
+  const Lane<N> L(blockIdx.x, threadIdx.x, B);
   Row<N> R;
 #pragma unroll
   for (int k = 0; k < G::HD; ++k) R.h[k] = 0u;
-  R.bk = R.wt = R.ab = R.aw = R.legal = 0u;
+  R.bk = R.wt = R.ab = R.aw = 0u;
   Meta m;
   m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0; m.bp = 0; m.episode = 0u; m.illegal = 0u;
   if (L.boardok) {
@@ -671,19 +850,20 @@ __global__ void __launch_bounds__(64) go_import_kernel(uint4* planes, uint4* met
   const uint32_t E = L.full & ~(R.bk | R.wt);
   uint32_t visited = 0u;
   for (;;) {
+    // next unvisited stone of every board, its whole chain, its liberty class
     const uint32_t rest = (R.bk | R.wt) & ~visited;
     const uint64_t has = __ballot(rest != 0u);
     if (has == 0ull) break;
-    const uint64_t mine = has & L.seg;
+    const uint64_t mine = has & (((uint64_t)L.seghi << 32) | L.seglo);
     const bool first = mine != 0ull && (__ffsll((long long)mine) - 1) == L.lane;
     const uint32_t seed = first ? (rest & (0u - rest)) : 0u;
-    const bool black = any_in_board((seed & R.bk) != 0u, L.seg);
-    uint32_t F; int cls;
-    flood_libs<false>(seed, black ? R.bk : R.wt, E, L.seg, F, cls);
+    const bool black = board_any((seed & R.bk) != 0u, L.seglo, L.seghi);
+    const uint32_t F = flood_plain(seed, black ? R.bk : R.wt);
+    bool one, two;
+    board_count(dilate(F) & E, L.seglo, L.seghi, one, two);
     visited |= F;
-    if (cls == 1) { if (black) R.ab |= F; else R.aw |= F; }
+    if (one) { if (black) R.ab |= F; else R.aw |= F; }
   }
-  R.legal = legal_row<N>(L, R, m.wtm, m.ko);
   store_row<N>(planes, (size_t)B * N, L, R);
   if (L.valid && L.r == 0) {
     meta[L.b] = pack_meta(m);
@@ -703,7 +883,7 @@ template <int N>
 size_t state_bytes_for(int B, size_t* off_meta, size_t* off_rew, size_t* off_term) {
   using G = Geo<N>;
   size_t o = 0;
-  o += align_up((size_t)G::NQ * B * N * sizeof(uint4), 256);
+  o += align_up((size_t)B * N * G::row_bytes, 256);
   if (off_meta) *off_meta = o;
   o += align_up((size_t)B * sizeof(uint4), 256);
   if (off_rew) *off_rew = o;
@@ -746,11 +926,13 @@ int launch_reset(pgxgo_ctx* h, int first) {
 
 template <int N>
 unsigned waves_for(int B) { return (unsigned)((B + Geo<N>::W - 1) / Geo<N>::W); }
+template <int N>
+unsigned blocks_for(int B) { return (waves_for<N>(B) + kWavesPerBlock - 1) / kWavesPerBlock; }
 
 template <int N>
 int launch_emit(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {
-  hipLaunchKernelGGL(go_emit_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, mask, h->mask_pitch, obs,
-                     h->obs_pitch);
+  hipLaunchKernelGGL(go_emit_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
+                     h->mask_pitch, obs, h->obs_pitch);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -760,19 +942,26 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   StepArgs a;
   a.planes = h->planes; a.meta = h->meta; a.actions = actions; a.rew = h->rew_out; a.term = h->term_out;
   a.mask = h->mask_out; a.obs = h->obs_out; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
-  a.B = h->B; a.seed = h->seed; a.komi_x2 = h->komi_x2; a.max_steps = h->max_steps; a.auto_reset = h->auto_reset;
+  a.B = h->B; a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
-  if (sample) hipLaunchKernelGGL((go_step_kernel<N, true>), dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, a);
-  else hipLaunchKernelGGL((go_step_kernel<N, false>), dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, a);
+  const dim3 grid(blocks_for<N>(h->B)), block(64 * kWavesPerBlock);
+  if (sample) hipLaunchKernelGGL((go_step_kernel<N, true>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_kernel<N, false>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
 
 template <int N>
 int launch_random(pgxgo_ctx* h, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* actions) {
-  const int threads = 64;
-  hipLaunchKernelGGL(go_random_actions_kernel<N>, dim3((h->B + threads - 1) / threads), dim3(threads), 0, h->stream, h->planes, h->B, seed, t,
-                     start_t, actions);
+  hipLaunchKernelGGL(go_random_actions_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B,
+                     seed, t, start_t, actions);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
+  hipLaunchKernelGGL(go_rollout_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -884,6 +1073,19 @@ int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint
   if (!h || !actions_dev || !next_actions_dev || next_actions_dev == actions_dev) return PGXGO_EINVAL;
   return DISPATCH_N(h, launch_step<19>(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev),
                     launch_step<9>(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev));
+}
+
+int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev, int32_t* actions_dev,
+                  float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev) {
+  if (!h || steps < 0 || slices < 1) return PGXGO_EINVAL;
+  if (steps == 0) return PGXGO_OK;
+  RolloutArgs a;
+  a.planes = h->planes; a.meta = h->meta; a.B = h->B;
+  a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
+  a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
+  a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
+  a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
+  return DISPATCH_N(h, launch_rollout<19>(h, a), launch_rollout<9>(h, a));
 }
 
 int pgxgo_random_actions(pgxgo_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev) {

@@ -194,3 +194,50 @@ def test_benchmark_configs_full_size(ci):
     assert bool((obs.max() <= 1))
     if not cfg.auto_reset:
         assert bool((g["terminated"] == 1).all())
+
+
+@pytest.mark.parametrize("N,B,T,slices,auto_reset", [(9, 100, 200, 200, True), (19, 50, 300, 300, True), (19, 64, 120, 1, False), (9, 13, 90, 7, True)])
+def test_rollout_kernel_equals_stepwise_play(N, B, T, slices, auto_reset):
+    """One launch of `T` plies (state kept in registers) against the oracle stepping ply by ply: every slice of
+    the recorded trajectory and the final state."""
+    import paper_2303_17503_amd as pg
+    seed = N * 1000 + B
+    env = pg.GoEnv(B, N, seed=seed, auto_reset=auto_reset)
+    orc = oracle.GoOracle(B, N, seed=seed, auto_reset=auto_reset)
+    start = (np.arange(B) % 5 * 3).astype(np.int32)
+    S, P = slices, N * N
+    acts = torch.full((S, B), -9, dtype=torch.int32, device="cuda")
+    rew = torch.full((S, B, 2), 7.0, dtype=torch.float32, device="cuda")
+    term = torch.full((S, B), 9, dtype=torch.uint8, device="cuda")
+    mask = torch.full((S, B, P + 1), 9, dtype=torch.uint8, device="cuda")
+    obs = torch.full((S, B, P * 17), 9, dtype=torch.uint8, device="cuda")
+    # two launches back to back: the second continues from the stored state
+    T1 = T // 3
+    env.rollout(T1, seed, 0, start_t=torch.as_tensor(start, device="cuda"), slices=S, actions=acts, rewards=rew, terminated=term, mask=mask, obs=obs)
+    first = [x.cpu().numpy().copy() for x in (acts, rew, term, mask, obs)]
+    env.rollout(T - T1, seed, T1, start_t=torch.as_tensor(start, device="cuda"), slices=S, actions=acts, rewards=rew, terminated=term, mask=mask, obs=obs)
+    second = [x.cpu().numpy() for x in (acts, rew, term, mask, obs)]
+    for t in range(T):
+        a = orc.random_actions(seed, t, start)
+        orc.step(a)
+        i = t % S if t < T1 else (t - T1) % S
+        # a slice can be checked if no later ply of the same launch overwrote it
+        src = first if t < T1 else second
+        n_launch = T1 if t < T1 else T - T1
+        base = 0 if t < T1 else T1
+        if (t - base) + S < n_launch:
+            continue
+        g_a, g_r, g_t, g_m, g_o = (x[i] for x in src)
+        assert (g_a == a).all(), f"actions t={t}"
+        assert (g_m == orc.legal_mask()).all(), f"mask t={t}"
+        assert (g_o.reshape(B, N, N, 17) == orc.observe()).all(), f"obs t={t}"
+        waiting = a < 0
+        assert (g_r[~waiting] == orc.rewards()[~waiting]).all() and (g_r[waiting] == 0).all(), f"rewards t={t}"
+        assert (g_t[~waiting] == orc.terminated()[~waiting]).all() and (g_t[waiting] == 0).all(), f"terminated t={t}"
+    g, c = env.export_state(), orc.export_state()
+    for name in ("board", "history", "ko", "to_play", "steps", "passes", "terminated", "black_player", "episode"):
+        assert (g[name].cpu().numpy().astype(np.int64) == getattr(c, name).astype(np.int64)).all(), name
+    assert (env.legal_mask().cpu().numpy() == orc.legal_mask()).all()
+    # and ordinary stepping continues from there
+    a = env.random_actions(seed, T)
+    assert (a.cpu().numpy() == orc.random_actions(seed, T)).all()
