@@ -82,8 +82,11 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=3, help="index into workloads.CONFIGS (3 = headline)")
-    ap.add_argument("--mode", choices=["fused", "separate"], default="fused",
-                    help="fused: the step kernel also draws the next action; separate: sampler kernel + step kernel")
+    ap.add_argument("--mode", choices=["fused", "separate", "rollout"], default="fused",
+                    help="fused: one launch per ply, the step kernel also draws the next action (headline); separate: sampler kernel + "
+                         "step kernel per ply; rollout: --rollout-len plies per launch with the state kept in registers")
+    ap.add_argument("--rollout-len", type=int, default=50, help="plies per launch in rollout mode")
+    ap.add_argument("--rollout-slices", type=int, default=1, help="trajectory slices the rollout writes to (1 = overwrite one set of buffers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-obs", action="store_true", help="do not emit the observation (not the headline metric)")
     args = ap.parse_args()
@@ -104,50 +107,71 @@ def main():
     with_obs = not args.no_obs
 
     env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
-    mask = env.new_mask()
-    obs = env.new_obs() if with_obs else None
-    rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
-    term = torch.zeros(B, dtype=torch.uint8, device="cuda")
-    env.bind_outputs(mask, obs, rew, term)
     start = workloads.start_times(cfg)
     start_dev = None if start is None else torch.as_tensor(start, device="cuda")
-    acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
-    t_base = 0
+    pre = cfg.warmup_max          # config 4: the plies that build the mid-game positions are not part of the measurement
+    P = N * N
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
-    def run_steps(t0, n, events=None):
-        """n passes of the hot path for launches t0..t0+n-1; acts[t & 1] holds the actions of launch t."""
-        for i in range(n):
-            t = t0 + i
-            if events is not None:
-                events[i][0].record()
-            if args.mode == "fused":
-                env.step_sample(acts[t & 1], seed, t + 1, start_dev, out=acts[(t + 1) & 1])
-            else:
-                env.step(acts[t & 1])
-            if events is not None:
-                events[i][1].record()
-            if args.mode != "fused":
-                env.random_actions(seed, t + 1, start_dev, out=acts[(t + 1) & 1])
+    if args.mode == "rollout":
+        S, Lr = args.rollout_slices, args.rollout_len
+        assert K % Lr == 0 and (pre + Wm) >= 0, "--steps must be a multiple of --rollout-len"
+        bufs = dict(actions=torch.empty((S, B), dtype=torch.int32, device="cuda"),
+                    rewards=torch.empty((S, B, 2), dtype=torch.float32, device="cuda"),
+                    terminated=torch.empty((S, B), dtype=torch.uint8, device="cuda"),
+                    mask=torch.empty((S, B, P + 1), dtype=torch.uint8, device="cuda"),
+                    obs=torch.empty((S, B, P * 17), dtype=torch.uint8, device="cuda") if with_obs else None)
+        if pre + Wm:
+            env.rollout(pre + Wm, seed, 0, start_t=start_dev, slices=S, **bufs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for i in range(K // Lr):
+            env.rollout(Lr, seed, pre + Wm + i * Lr, start_t=start_dev, slices=S, **bufs)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        kern_ms = ev0.elapsed_time(ev1) / K       # per ply: the launch covers rollout_len plies
+        kname = "go_rollout_kernel<%d>" % N
+    else:
+        mask = env.new_mask()
+        obs = env.new_obs() if with_obs else None
+        rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
+        term = torch.zeros(B, dtype=torch.uint8, device="cuda")
+        env.bind_outputs(mask, obs, rew, term)
+        acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
 
-    # config 4: the warm-up plies that build the mid-game positions are not part of the measurement
-    pre = cfg.warmup_max
-    env.random_actions(seed, 0, start_dev, out=acts[0])
-    run_steps(0, pre + Wm)
-    t_base = pre + Wm
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(t_base, K)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    t_base += K
+        def run_steps(t0, n, events=None):
+            """n passes of the hot path for launches t0..t0+n-1; acts[t & 1] holds the actions of launch t."""
+            for i in range(n):
+                t = t0 + i
+                if args.mode == "fused":
+                    env.step_sample(acts[t & 1], seed, t + 1, start_dev, out=acts[(t + 1) & 1])
+                else:
+                    if events is not None: events[i][0].record()
+                    env.step(acts[t & 1])
+                    if events is not None: events[i][1].record()
+                    env.random_actions(seed, t + 1, start_dev, out=acts[(t + 1) & 1])
 
-    # per-launch duration of the step kernel: HIP events on the stream the kernels run on
-    n_ev = min(K, 500)
-    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
-    run_steps(t_base, n_ev, events)
-    torch.cuda.synchronize()
-    kern_ms = sum(a.elapsed_time(b) for a, b in events) / n_ev
-    t_base += n_ev
+        env.random_actions(seed, 0, start_dev, out=acts[0])
+        run_steps(0, pre + Wm)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        run_steps(pre + Wm, K)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        if args.mode == "fused":
+            # the timed region is K launches of the one kernel, back to back on the stream the events are on
+            kern_ms = ev0.elapsed_time(ev1) / K
+        else:
+            n_ev = min(K, 500)
+            events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+            run_steps(pre + Wm + K, n_ev, events)
+            torch.cuda.synchronize()
+            kern_ms = sum(a.elapsed_time(b) for a, b in events) / n_ev
+        kname = "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
 
     # a plain device copy of the same number of bytes as one step writes, as a practical ceiling
     nbytes = B * (N * N * 17 + N * N + 1)
@@ -162,7 +186,6 @@ def main():
 
     bytes_ply = algorithmic_bytes_per_ply(N, with_obs)
     achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
-    kname = "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
     traffic = read_traffic(os.path.join(ROOT, "profiles", f"go_step_kernel_{cfg.name}_pmc.txt")) if with_obs and args.mode == "fused" else None
     out = {
         "metric": "Go env steps/sec on 1 MI355X (19x19, batch 16384, random legal play); HBM GB/s % peak",
@@ -178,7 +201,8 @@ def main():
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "board_size": N, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset,
-                   "observation": with_obs, "mode": args.mode, "komi": cfg.komi_x2 / 2, "pre_warmup_plies_max": cfg.warmup_max},
+                   "observation": with_obs, "mode": args.mode, "komi": cfg.komi_x2 / 2, "pre_warmup_plies_max": cfg.warmup_max,
+                   **({"rollout_len": args.rollout_len, "rollout_slices": args.rollout_slices} if args.mode == "rollout" else {})},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
