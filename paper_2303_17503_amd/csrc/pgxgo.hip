@@ -48,6 +48,14 @@ thread_local int g_last_hip = 0;
 #endif
 constexpr int kWavesPerBlock = PGXGO_WAVES_PER_BLOCK;   // wavefronts never synchronise with each other; this only shapes the launch
 
+#ifdef PGXGO_TRACE
+// Build-time option for timing studies: wavefront w writes its shader clock at mark k to trace[w * 8 + k].
+__device__ unsigned long long* g_trace = nullptr;
+#define TRACE_MARK(wave, k) do { if (g_trace && (threadIdx.x & 63) == 0) g_trace[(size_t)(wave) * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define TRACE_MARK(wave, k) do { } while (0)
+#endif
+
 // ------------------------------------------------------------------------------------------------
 // geometry
 // ------------------------------------------------------------------------------------------------
@@ -138,7 +146,9 @@ __device__ __forceinline__ void board_count(uint32_t w, uint32_t seglo, uint32_t
 // connected component(s) of `seed` inside S
 __device__ __forceinline__ uint32_t flood_plain(uint32_t seed, uint32_t S) {
   uint32_t F = seed;
-  for (;;) {
+  for (;;) {   // three growth steps per convergence test: the test (ballot, scalar branch) costs as much as a step
+    F |= dilate(F) & S;
+    F |= dilate(F) & S;
     uint32_t G = F | (dilate(F) & S);
     bool ch = G != F;
     F = G;
@@ -218,6 +228,30 @@ __device__ __forceinline__ void store_row(uint4* __restrict__ planes, size_t row
   }
 }
 
+// Stores only the planes of this row whose content differs from `Old` (what the kernel loaded).  With colours
+// stored absolutely, a history word changes only while its point changed within the last 8 plies, so most
+// rows of most planes are unchanged from ply to ply.
+template <int N>
+__device__ __forceinline__ void store_row_changed(uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, const Row<N>& R, const Row<N>& Old) {
+  using G = Geo<N>;
+  uint32_t rec[G::NQ * 4 + 4], old[G::NQ * 4 + 4];
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) { rec[k] = R.h[k]; old[k] = Old.h[k]; }
+  rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw;
+  old[G::HD] = Old.bk; old[G::HD + 1] = Old.wt; old[G::HD + 2] = Old.ab; old[G::HD + 3] = Old.aw;
+  if (L.valid) {
+    const size_t idx = (size_t)L.b * N + L.r;
+#pragma unroll
+    for (int k = 0; k < G::NQ; ++k) {
+      const uint32_t diff = (rec[4 * k] ^ old[4 * k]) | (rec[4 * k + 1] ^ old[4 * k + 1]) | (rec[4 * k + 2] ^ old[4 * k + 2]) | (rec[4 * k + 3] ^ old[4 * k + 3]);
+      if (diff) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
+    }
+    uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
+    if constexpr (G::REM == 2) { if ((rec[4 * G::NQ] ^ old[4 * G::NQ]) | (rec[4 * G::NQ + 1] ^ old[4 * G::NQ + 1])) *(uint2*)(tail + idx * 2) = make_uint2(rec[4 * G::NQ], rec[4 * G::NQ + 1]); }
+    if constexpr (G::REM == 1) { if (rec[4 * G::NQ] != old[4 * G::NQ]) tail[idx] = rec[4 * G::NQ]; }
+  }
+}
+
 // legal points of the player to move (Fig. 2 legal_action_mask, pass excluded): empty, not the ko point, and
 // next to an empty point, or to an own chain that is not in atari, or to an opposing chain that is
 template <int N>
@@ -282,80 +316,92 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   }
 }
 
-// Legal mask bytes [N*N+1] and observation bytes [N][N][17] of every board of the wavefront.
+// Legal mask bytes [N*N+1] of every board of the wavefront.
+template <int N>
+__device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
+                                          uint32_t* lds_mask, const uint2* lut) {
+  using G = Geo<N>;
+  if (L.lane < G::W * G::MASK_DW) lds_mask[L.lane] = 0u;
+  static_assert(G::W * G::MASK_DW <= 64, "mask staging is cleared by one store per lane");
+  wave_lds_fence();
+  if (L.valid) {
+    uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u);
+    uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
+    uint32_t* reg = lds_mask + L.j * G::MASK_DW;
+    atomicOr(&reg[q], legal << s);
+    if (s + N > 32u) atomicOr(&reg[q + 1], legal >> (32u - s));
+    if (L.r == 0) { uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int jj = 0; jj < G::W; ++jj) {
+    const int bb = wave * G::W + jj;
+    if (bb < B) emit_bytes<G::A, G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)bb * mask_pitch, L.lane);
+  }
+  wave_lds_fence();
+}
+
+// Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
+template <int N>
+__device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
+                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut) {
+  using G = Geo<N>;
+  // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
+  // then the colour bit (Appendix C "Go", Observation); a row is N such pieces back to back.
+  uint32_t S[G::NR];
+#pragma unroll
+  for (int k = 0; k < G::NR; ++k) S[k] = 0u;
+  const uint32_t cb = wtm ? 0u : 1u;
+  const uint32_t swapmask = wtm ? 0x55555555u : 0u;
+#pragma unroll
+  for (int jd = 0; jd < G::HD; ++jd) {
+    uint32_t w = h[jd];
+    uint32_t x = (w ^ (w >> 1)) & swapmask;
+    w ^= x | (x << 1);
+    uint32_t lo17 = (w & 0xFFFFu) | (cb << 16);
+    uint32_t hi17 = (2 * jd + 1 < N) ? ((w >> 16) | (cb << 16)) : 0u;
+    uint32_t low32 = lo17 | (hi17 << 17), high2 = hi17 >> 15;
+    const int pos = 34 * jd, k = pos >> 5, sh = pos & 31;
+    S[k] |= low32 << sh;
+    if (k + 1 < G::NR) S[k + 1] |= sh ? ((low32 >> (32 - sh)) | (high2 << sh)) : high2;
+  }
+  {
+    uint4* z = (uint4*)lds_obs;
+    constexpr int NZ = G::W * G::OBS_DW / 4;
+#pragma unroll
+    for (int i = 0; i < (NZ + 63) / 64; ++i)
+      if (i * 64 + 63 < NZ || i * 64 + L.lane < NZ) z[i * 64 + L.lane] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  wave_lds_fence();
+  if (L.valid) {
+    uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u);
+    uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
+    uint32_t* reg = lds_obs + L.j * G::OBS_DW + q;
+    // shifted string T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door
+    atomicOr(&reg[0], S[0] << s);
+#pragma unroll
+    for (int i = 1; i <= G::NR; ++i) {
+      uint32_t hi = (i < G::NR) ? S[i] : 0u;
+      uint32_t t = __funnelshift_l(S[i - 1], hi, s);
+      if (i <= G::NI) reg[i] = t;
+      else if (t) atomicOr(&reg[i], t);
+    }
+  }
+  wave_lds_fence();
+#pragma unroll
+  for (int jj = 0; jj < G::W; ++jj) {
+    const int bb = wave * G::W + jj;
+    if (bb < B) emit_bytes<G::OBS, G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)bb * obs_pitch, L.lane);
+  }
+  wave_lds_fence();
+}
+
 template <int N>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
                                              uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut) {
-  using G = Geo<N>;
-  if (mask) {
-    if (L.lane < G::W * G::MASK_DW) lds_mask[L.lane] = 0u;
-    static_assert(G::W * G::MASK_DW <= 64, "mask staging is cleared by one store per lane");
-    wave_lds_fence();
-    if (L.valid) {
-      uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u);
-      uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
-      uint32_t* reg = lds_mask + L.j * G::MASK_DW;
-      atomicOr(&reg[q], legal << s);
-      if (s + N > 32u) atomicOr(&reg[q + 1], legal >> (32u - s));
-      if (L.r == 0) { uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
-    }
-    wave_lds_fence();
-#pragma unroll
-    for (int jj = 0; jj < G::W; ++jj) {
-      const int bb = wave * G::W + jj;
-      if (bb < B) emit_bytes<G::A, G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)bb * mask_pitch, L.lane);
-    }
-  }
-  if (obs) {
-    // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
-    // then the colour bit (Appendix C "Go", Observation); a row is N such pieces back to back.
-    uint32_t S[G::NR];
-#pragma unroll
-    for (int k = 0; k < G::NR; ++k) S[k] = 0u;
-    const uint32_t cb = wtm ? 0u : 1u;
-    const uint32_t swapmask = wtm ? 0x55555555u : 0u;
-#pragma unroll
-    for (int jd = 0; jd < G::HD; ++jd) {
-      uint32_t w = R.h[jd];
-      uint32_t x = (w ^ (w >> 1)) & swapmask;
-      w ^= x | (x << 1);
-      uint32_t lo17 = (w & 0xFFFFu) | (cb << 16);
-      uint32_t hi17 = (2 * jd + 1 < N) ? ((w >> 16) | (cb << 16)) : 0u;
-      uint32_t low32 = lo17 | (hi17 << 17), high2 = hi17 >> 15;
-      const int pos = 34 * jd, k = pos >> 5, sh = pos & 31;
-      S[k] |= low32 << sh;
-      if (k + 1 < G::NR) S[k + 1] |= sh ? ((low32 >> (32 - sh)) | (high2 << sh)) : high2;
-    }
-    {
-      uint4* z = (uint4*)lds_obs;
-      constexpr int NZ = G::W * G::OBS_DW / 4;
-#pragma unroll
-      for (int i = 0; i < (NZ + 63) / 64; ++i)
-        if (i * 64 + 63 < NZ || i * 64 + L.lane < NZ) z[i * 64 + L.lane] = make_uint4(0u, 0u, 0u, 0u);
-    }
-    wave_lds_fence();
-    if (L.valid) {
-      uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u);
-      uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
-      uint32_t* reg = lds_obs + L.j * G::OBS_DW + q;
-      // shifted string T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door
-      atomicOr(&reg[0], S[0] << s);
-#pragma unroll
-      for (int i = 1; i <= G::NR; ++i) {
-        uint32_t hi = (i < G::NR) ? S[i] : 0u;
-        uint32_t t = __funnelshift_l(S[i - 1], hi, s);
-        if (i <= G::NI) reg[i] = t;
-        else if (t) atomicOr(&reg[i], t);
-      }
-    }
-    wave_lds_fence();
-#pragma unroll
-    for (int jj = 0; jj < G::W; ++jj) {
-      const int bb = wave * G::W + jj;
-      if (bb < B) emit_bytes<G::OBS, G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)bb * obs_pitch, L.lane);
-    }
-  }
+  if (mask) emit_mask<N>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut);
+  if (obs) emit_obs<N>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -409,28 +455,63 @@ struct Rules {
   int komi_x2, max_steps, auto_reset;
 };
 
-// skip: leave the board alone.  want_pass / want_point(pr,pc): the requested action; anything else is illegal.
+// What a requested action amounts to for a board (the same in every lane of the board).
+struct Move {
+  bool skip;      // leave the board alone
+  bool frozen;    // the game had ended before (no auto-reset): nothing changes, terminated is reported
+  bool is_pass, playing, illegal;
+  int pr, pc;     // the point when `playing`
+};
+
+// a1/a2.  want_pass / want_point(pr,pc): the requested action; anything else is illegal.
 // GATE: check the point against the mover's legal set (not needed for actions drawn from that set).
-// Out: rewards by player id, `flag` = the terminated output (game ended in this ply, or had ended before).
 template <int N, bool GATE>
-__device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, bool skip, bool want_pass, bool want_point,
-                                          int pr_in, int pc_in, float& rew0, float& rew1, bool& flag) {
-  using G = Geo<N>;
-  const bool frozen = !skip && m.term;
-  const bool live = !skip && !frozen;
-  const bool is_pass = live && want_pass;
+__device__ __forceinline__ Move gate_move(const Lane<N>& L, const Row<N>& R, const Meta& m, bool skip, bool want_pass, bool want_point,
+                                          int pr_in, int pc_in) {
+  Move mv;
+  mv.skip = skip;
+  mv.frozen = !skip && m.term;
+  const bool live = !skip && !mv.frozen;
+  mv.is_pass = live && want_pass;
   const bool on_board = live && want_point;
-  int pr = on_board ? pr_in : -100, pc = on_board ? pc_in : 0;
-  uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
-  bool playing = on_board;
+  mv.playing = on_board;
   if (GATE) {
+    const uint32_t pbit = (L.valid && on_board && L.r == pr_in) ? (1u << pc_in) : 0u;
     const uint32_t legal_now = legal_row<N>(L, R, m.wtm, m.ko);
-    playing = on_board && board_any((legal_now & pbit) != 0u, L.seglo, L.seghi);
+    mv.playing = on_board && board_any((legal_now & pbit) != 0u, L.seglo, L.seghi);
   }
-  const bool illegal = live && !is_pass && !playing;
-  if (!playing) { pr = -100; pbit = 0u; }
+  mv.illegal = live && !mv.is_pass && !mv.playing;
+  mv.pr = mv.playing ? pr_in : -100;
+  mv.pc = mv.playing ? pc_in : 0;
+  return mv;
+}
+
+// history push: every halfword shifts by one ply and takes the position (bk, wt) in its low bits
+template <int N>
+__device__ __forceinline__ void push_history(uint32_t (&h)[Geo<N>::HD], uint32_t bk, uint32_t wt, bool moved) {
+  const uint32_t lo = (bk & 0x55555555u) | ((wt & 0x55555555u) << 1);   // bit 2j / 2j+1: black / white at column 2j
+  const uint32_t hi = ((bk >> 1) & 0x55555555u) | (wt & 0xAAAAAAAAu);   // the same for column 2j+1
+#pragma unroll
+  for (int jd = 0; jd < Geo<N>::HD; ++jd) {
+    const uint32_t cur = ((lo >> (2 * jd)) & 3u) | (((hi >> (2 * jd)) & 3u) << 16);
+    const uint32_t pushed = ((h[jd] << 2) & 0xFFFCFFFCu) | cur;
+    h[jd] = moved ? pushed : h[jd];
+  }
+}
+
+// a3-a8 for every board of the wavefront; registers in, registers out.
+// Out: rewards by player id, `flag` = the terminated output (game ended in this ply, or had ended before),
+// `captured` = the stones this ply removed, `reset` = the board was re-initialised by auto-reset.
+template <int N>
+__device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, const Move& mv, float& rew0, float& rew1,
+                                           bool& flag, uint32_t& captured, bool& reset) {
+  using G = Geo<N>;
+  const bool playing = mv.playing, is_pass = mv.is_pass, illegal = mv.illegal, frozen = mv.frozen;
+  const int pr = mv.pr, pc = mv.pc;
+  const uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
   const int wtm0 = m.wtm;
   rew0 = 0.f; rew1 = 0.f;
+  captured = 0u;
 
   // ---- a3-a5: place the stone, capture, update the atari sets, ko ----------------------------------------
   if (__ballot(playing) != 0ull) {
@@ -448,6 +529,7 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
     const uint32_t capseed = nb & aopp;
     if (__ballot(capseed != 0u) != 0ull) {
       const uint32_t cap = flood_plain(capseed, aopp);
+      if (playing) captured = cap;
       opp &= ~cap; aopp &= ~cap;
       // own chains in atari next to the vacated points gain a liberty
       const uint32_t un = flood_plain(aown & dilate(cap), aown);
@@ -475,7 +557,14 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
     bool run2 = board_any(F2 != 0u, L.seglo, L.seghi), run3 = board_any(F3 != 0u, L.seglo, L.seghi);
     bool run4 = board_any(F4 != 0u, L.seglo, L.seghi);
     bool at0 = false, at1 = false, at2 = false, at3 = false, at4 = false;
-    auto flood_step = [&](uint32_t& F, uint32_t S, bool& run, bool& at) {
+    auto flood_step = [&](uint32_t& F, uint32_t S, bool& run, bool& at, bool first) {
+      if (!first) {   // after the first look, unexamined growth steps precede each examined one
+#ifndef PGXGO_BLIND
+#define PGXGO_BLIND 4
+#endif
+#pragma unroll
+        for (int b_ = 0; b_ < PGXGO_BLIND; ++b_) F |= dilate(F) & S;
+      }
       const uint32_t D = dilate(F);
       const uint32_t Gn = F | (D & S);
       bool one, two;
@@ -486,14 +575,16 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
       run = run && !two && !conv;
       F = Gn;
     };
+    bool first = true;
     for (;;) {
       const uint64_t r0 = __ballot(run0), r1 = __ballot(run1), r2 = __ballot(run2), r3 = __ballot(run3), r4 = __ballot(run4);
       if ((r0 | r1 | r2 | r3 | r4) == 0ull) break;
-      if (r0 != 0ull) flood_step(F0, own, run0, at0);
-      if (r1 != 0ull) flood_step(F1, opp, run1, at1);
-      if (r2 != 0ull) flood_step(F2, opp, run2, at2);
-      if (r3 != 0ull) flood_step(F3, opp, run3, at3);
-      if (r4 != 0ull) flood_step(F4, opp, run4, at4);
+      if (r0 != 0ull) flood_step(F0, own, run0, at0, first);
+      if (r1 != 0ull) flood_step(F1, opp, run1, at1, first);
+      if (r2 != 0ull) flood_step(F2, opp, run2, at2, first);
+      if (r3 != 0ull) flood_step(F3, opp, run3, at3, first);
+      if (r4 != 0ull) flood_step(F4, opp, run4, at4, first);
+      first = false;
     }
     aown |= at0 ? F0 : 0u;
     aopp |= (at1 ? F1 : 0u) | (at2 ? F2 : 0u) | (at3 ? F3 : 0u) | (at4 ? F4 : 0u);
@@ -510,17 +601,8 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
     m.steps += 1;
     m.wtm ^= 1;
   }
-  // ---- a6: history push: every halfword shifts by one ply and takes the new position in its low bits -----
-  {
-    const uint32_t lo = (R.bk & 0x55555555u) | ((R.wt & 0x55555555u) << 1);   // bit 2j / 2j+1: black / white at column 2j
-    const uint32_t hi = ((R.bk >> 1) & 0x55555555u) | (R.wt & 0xAAAAAAAAu);   // the same for column 2j+1
-#pragma unroll
-    for (int jd = 0; jd < G::HD; ++jd) {
-      const uint32_t cur = ((lo >> (2 * jd)) & 3u) | (((hi >> (2 * jd)) & 3u) << 16);
-      const uint32_t pushed = ((R.h[jd] << 2) & 0xFFFCFFFCu) | cur;
-      R.h[jd] = moved ? pushed : R.h[jd];
-    }
-  }
+  // ---- a6: history push ---------------------------------------------------------------------------------
+  push_history<N>(R.h, R.bk, R.wt, moved);
 
   // ---- a7: termination and Tromp-Taylor area score ------------------------------------------------------
   const bool score = moved && (m.passes >= 2 || m.steps >= cfg.max_steps);
@@ -550,6 +632,7 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
     m.illegal += 1;
   }
   const bool ended = score || illegal;
+  reset = ended && cfg.auto_reset != 0;
   if (ended) {
     m.term = 1;
     // ---- a8: auto-reset (Sec. 4.1) -------------------------------------------------------------------------
@@ -563,6 +646,15 @@ __device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, 
     }
   }
   flag = ended || frozen;
+}
+
+template <int N, bool GATE>
+__device__ __forceinline__ void step_core(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, bool skip, bool want_pass, bool want_point,
+                                          int pr_in, int pc_in, float& rew0, float& rew1, bool& flag) {
+  const Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
+  uint32_t captured;
+  bool reset;
+  apply_move<N>(L, R, m, cfg, mv, rew0, rew1, flag, captured, reset);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -591,37 +683,50 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
-  fill_spread_table(lut);
   const int wib = threadIdx.x >> 6;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
-  if (wave * G::W >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
-  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  const Lane<N> L(wave, threadIdx.x & 63, a.B);   // in a wavefront beyond the batch no lane is valid
   const size_t rows_total = (size_t)a.B * N;
+  TRACE_MARK(wave, 0);
 
+  // the loads are issued first and fly while the block fills its lookup table
   Row<N> R;
   load_row<N>(a.planes, rows_total, L, R);
-  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
+  const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
+  fill_spread_table(lut);
+  if (wave * G::W >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
+  const Row<N> R_loaded = R;
+  Meta m = unpack_meta(meta_raw);
 
-  // a1: decode the action
+  // a1/a2: decode the action and gate it
   const bool skip = !L.boardok || act == -1;
   const bool in_range = act >= 0 && act < G::P;
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
+  const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
+  TRACE_MARK(wave, 1);
+
+  // a3-a8
   float rew0, rew1;
-  bool flag;
-  step_core<N, true>(L, R, m, a.rules, skip, act == G::P, in_range, pr, pc, rew0, rew1, flag);
+  bool flag, reset;
+  uint32_t captured;
+  apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
   if (!skip && L.valid && L.r == 0) {
     *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
 
-  // ---- a9/a10: legal mask and observation of the player now to move --------------------------------------
+  TRACE_MARK(wave, 3);
+  // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
+  if (a.obs) emit_obs<N>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  TRACE_MARK(wave, 4);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  emit_outputs<N>(L, R, legal, m.wtm, wave, a.B, a.mask, a.mask_pitch, a.obs, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
+  if (a.mask) emit_mask<N>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
 
+  TRACE_MARK(wave, 5);
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
-    store_row<N>(a.planes, rows_total, L, R);
+    store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
     if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
   }
   if (SAMPLE) {
@@ -629,6 +734,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
     const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
   }
+  TRACE_MARK(wave, 6);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1144,6 +1250,13 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
   return PGXGO_OK;
 }
+
+#ifdef PGXGO_TRACE
+int pgxgo_debug_set_trace(unsigned long long* trace_dev) {
+  HIPCHK(hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &trace_dev, sizeof(trace_dev)));
+  return PGXGO_OK;
+}
+#endif
 
 int pgxgo_sync(pgxgo_t h) {
   if (!h) return PGXGO_EINVAL;
