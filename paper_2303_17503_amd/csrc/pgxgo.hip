@@ -55,6 +55,7 @@ __device__ unsigned long long* g_trace = nullptr;
 #else
 #define TRACE_MARK(wave, k) do { } while (0)
 #endif
+#define TRACE_HERE(k) TRACE_MARK(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), k)
 
 // ------------------------------------------------------------------------------------------------
 // geometry
@@ -292,20 +293,16 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   uint8_t* base = dst - head;
   const uint32_t total = head + NBYTES;
   const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1; m1 - m0 <= NBYTES/16 <= 64*ROUNDS
-  const uint16_t* b16 = (const uint16_t*)bits;
+  const uint32_t mine = m0 + (uint32_t)lane;             // this lane's group in round 0; round i adds 64*i
+  const uint16_t* src = (const uint16_t*)bits + mine;
+  uint4* out = (uint4*)base + mine;
   uint32_t v[ROUNDS];
 #pragma unroll
-  for (int i = 0; i < ROUNDS; ++i) {
-    const uint32_t m = m0 + 64u * i + lane;
-    v[i] = (i + 1 < ROUNDS || m < m1) ? b16[m] : 0u;
-  }
+  for (int i = 0; i < ROUNDS; ++i) v[i] = (i + 1 < ROUNDS || mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
 #pragma unroll
   for (int i = 0; i < ROUNDS; ++i) {
-    const uint32_t m = m0 + 64u * i + lane;
     const uint2 lo = lut[v[i] & 255u], hi = lut[v[i] >> 8];
-    if (i + 1 < ROUNDS || m < m1) {
-      *(uint4*)(base + 16u * m) = make_uint4(lo.x, lo.y, hi.x, hi.y);
-    }
+    if (i + 1 < ROUNDS || mine + 64u * i < m1) out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
   }
   if (lane < 32) {
     uint32_t i = lane & 15u, pos;
@@ -544,6 +541,7 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
       const int p = pr * N + pc;
       if (cap1 && lib1 && lone) ko_new = cN ? p - N : cS ? p + N : cW ? p - 1 : p + 1;
     }
+    TRACE_HERE(2);
     const uint32_t E = L.full & ~(own | opp);
     // own chains in atari that the new stone joins stop being chains of their own
     const uint32_t clrseed = friends & aown;
@@ -586,6 +584,7 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
       if (r4 != 0ull) flood_step(F4, opp, run4, at4, first);
       first = false;
     }
+    TRACE_HERE(7);
     aown |= at0 ? F0 : 0u;
     aopp |= (at1 ? F1 : 0u) | (at2 ? F2 : 0u) | (at3 ? F3 : 0u) | (at4 ? F4 : 0u);
     if (playing) {
@@ -670,6 +669,7 @@ struct StepArgs {
   uint8_t* obs;
   int64_t mask_pitch, obs_pitch;
   int B;
+  int sparse_store;
   Rules rules;
   // fused sampler
   uint32_t sample_seed, sample_t;
@@ -726,7 +726,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
   TRACE_MARK(wave, 5);
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
-    store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
+    // Writing only the changed planes pays while state and outputs stay resident in the memory-side cache
+    // (partial lines merge there); beyond it partial lines cost a read-modify-write in DRAM and whole rows win.
+    if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
+    else store_row<N>(a.planes, rows_total, L, R);
     if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
   }
   if (SAMPLE) {
@@ -1050,6 +1053,9 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   a.mask = h->mask_out; a.obs = h->obs_out; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
   a.B = h->B; a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
+  // bytes one ply touches: state rows + outputs; 256 MB of memory-side cache on this part, keep a margin
+  const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
+  a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
   const dim3 grid(blocks_for<N>(h->B)), block(64 * kWavesPerBlock);
   if (sample) hipLaunchKernelGGL((go_step_kernel<N, true>), grid, block, 0, h->stream, a);
   else hipLaunchKernelGGL((go_step_kernel<N, false>), grid, block, 0, h->stream, a);

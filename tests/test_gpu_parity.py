@@ -241,3 +241,91 @@ def test_rollout_kernel_equals_stepwise_play(N, B, T, slices, auto_reset):
     # and ordinary stepping continues from there
     a = env.random_actions(seed, T)
     assert (a.cpu().numpy() == orc.random_actions(seed, T)).all()
+
+
+@pytest.mark.parametrize("N,B,komi_x2,max_steps", [(9, 1, 0, 40), (9, 7, 13, 0), (19, 2, -3, 100), (9, 65, 14, 161)])
+def test_options_komi_and_ply_cap(N, B, komi_x2, max_steps):
+    """Non-default komi (even: draws possible; negative) and ply caps, tiny and ragged batches."""
+    from gpu_common import Pair
+    p = Pair(B, N, seed=17, auto_reset=True, komi_x2=komi_x2, max_steps=max_steps)
+    T = 3 * (max_steps or 2 * N * N) + 5
+    p.rollout(17, 0, T, every=1, state_every=20)
+    assert p.orc.export_state().episode.min() >= 2
+
+
+def test_mask_only_and_obs_only_bindings():
+    from gpu_common import Pair
+    import paper_2303_17503_amd as pg
+    B, N = 20, 9
+    p = Pair(B, N, seed=9, auto_reset=True, bind=False)
+    mask, obs = p.env.new_mask(), p.env.new_obs()
+    for t in range(60):
+        p.env.bind_outputs(mask if t % 2 == 0 else None, obs if t % 3 == 0 else None, None, None)
+        a = p.env.random_actions(9, t)
+        a_c = p.orc.random_actions(9, t)
+        assert (a.cpu().numpy() == a_c).all()
+        p.step(a, a_c)
+        if t % 2 == 0:
+            assert (mask.cpu().numpy() == p.orc.legal_mask()).all()
+        if t % 3 == 0:
+            assert (obs.cpu().numpy().reshape(B, N, N, 17) == p.orc.observe()).all()
+        assert (p.env.rewards().cpu().numpy() == p.orc.rewards()).all()
+        assert (p.env.terminated().cpu().numpy() == p.orc.terminated()).all()
+    p.env.bind_outputs(None, None, None, None)
+
+
+def test_import_with_ko_and_finished_games():
+    """Positions with a live ko ban, and games already over, survive import: the ban is honoured and the
+    finished games stay frozen."""
+    from gpu_common import Pair
+    N, B = 9, len(pos.SCRIPTS)
+    src = oracle.GoOracle(B, N, seed=5)
+    names = sorted(pos.SCRIPTS)
+    T = max(len(pos.SCRIPTS[n]["moves"]) for n in names)
+    for t in range(T):
+        a = np.array([pos.idx(pos.SCRIPTS[n]["moves"][t]) if t < len(pos.SCRIPTS[n]["moves"]) else -1 for n in names], np.int32)
+        src.step(a)
+    st = src.export_state()
+    assert (st.ko >= 0).sum() >= 3
+    st.terminated[::4] = 1                     # every fourth game is declared over
+    p = Pair(B, N, seed=5, auto_reset=False)
+    p.orc.import_state(st)
+    dev = {k: torch.as_tensor(getattr(st, k), device="cuda") for k in st.__slots__}
+    dev["episode"] = dev["episode"].to(torch.int32)
+    p.env.import_state(dev)
+    p.compare("after import")
+    p.rollout(6, 50, 90, every=1, state_every=10)
+    after = p.env.export_state()
+    assert (after["board"].cpu().numpy()[::4] == st.board[::4]).all()
+
+
+def test_rollout_single_slice_with_staggered_start_at_full_batch():
+    """The rollout kernel in the launch shape the benchmark uses (16384 games, one slice), checked on a seeded
+    sample of environments at the end of every launch."""
+    import paper_2303_17503_amd as pg
+    B, N, seed, P = 16384, 19, 3, 361
+    ids = np.array(sorted({0, 1, 2, 3, 5000, 5001, 16381, 16382, 16383} | set(np.random.default_rng(1).choice(B, 24, replace=False).tolist())), np.int32)
+    env = pg.GoEnv(B, N, seed=seed, auto_reset=True)
+    orc = oracle.GoOracle(len(ids), N, seed=seed, auto_reset=True, env_ids=ids)
+    start = (np.arange(B) % 7).astype(np.int32)
+    sel = torch.as_tensor(ids.astype(np.int64), device="cuda")
+    acts = torch.empty((1, B), dtype=torch.int32, device="cuda")
+    rew = torch.empty((1, B, 2), dtype=torch.float32, device="cuda")
+    term = torch.empty((1, B), dtype=torch.uint8, device="cuda")
+    mask = torch.empty((1, B, P + 1), dtype=torch.uint8, device="cuda")
+    obs = torch.empty((1, B, P * 17), dtype=torch.uint8, device="cuda")
+    t = 0
+    for L in (1, 2, 50, 50, 97, 400):
+        env.rollout(L, seed, t, start_t=torch.as_tensor(start, device="cuda"), slices=1, actions=acts, rewards=rew, terminated=term, mask=mask, obs=obs)
+        for i in range(L):
+            a = orc.random_actions(seed, t + i, start[ids])
+            orc.step(a)
+        t += L
+        assert (acts[0].index_select(0, sel).cpu().numpy() == a).all()
+        assert (mask[0].index_select(0, sel).cpu().numpy() == orc.legal_mask()).all(), t
+        assert (obs[0].index_select(0, sel).cpu().numpy().reshape(-1, N, N, 17) == orc.observe()).all(), t
+        assert (rew[0].index_select(0, sel).cpu().numpy() == orc.rewards()).all(), t
+        assert (term[0].index_select(0, sel).cpu().numpy() == orc.terminated()).all(), t
+    g = env.export_state()
+    assert (g["board"].index_select(0, sel).cpu().numpy() == orc.export_state().board).all()
+    assert int(g["episode"].max()) >= 1
