@@ -48,14 +48,6 @@ thread_local int g_last_hip = 0;
 #endif
 constexpr int kWavesPerBlock = PGXGO_WAVES_PER_BLOCK;   // wavefronts never synchronise with each other; this only shapes the launch
 
-#ifdef PGXGO_TRACE
-// Build-time option for timing studies: wavefront w writes its shader clock at mark k to trace[w * 8 + k].
-__device__ unsigned long long* g_trace = nullptr;
-#define TRACE_MARK(wave, k) do { if (g_trace && (threadIdx.x & 63) == 0) g_trace[(size_t)(wave) * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define TRACE_MARK(wave, k) do { } while (0)
-#endif
-#define TRACE_HERE(k) TRACE_MARK(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), k)
 
 // ------------------------------------------------------------------------------------------------
 // geometry
@@ -541,7 +533,6 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
       const int p = pr * N + pc;
       if (cap1 && lib1 && lone) ko_new = cN ? p - N : cS ? p + N : cW ? p - 1 : p + 1;
     }
-    TRACE_HERE(2);
     const uint32_t E = L.full & ~(own | opp);
     // own chains in atari that the new stone joins stop being chains of their own
     const uint32_t clrseed = friends & aown;
@@ -584,7 +575,6 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
       if (r4 != 0ull) flood_step(F4, opp, run4, at4, first);
       first = false;
     }
-    TRACE_HERE(7);
     aown |= at0 ? F0 : 0u;
     aopp |= (at1 ? F1 : 0u) | (at2 ? F2 : 0u) | (at3 ? F3 : 0u) | (at4 ? F4 : 0u);
     if (playing) {
@@ -678,7 +668,7 @@ struct StepArgs {
 };
 
 template <int N, bool SAMPLE>
-__global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -687,7 +677,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   const Lane<N> L(wave, threadIdx.x & 63, a.B);   // in a wavefront beyond the batch no lane is valid
   const size_t rows_total = (size_t)a.B * N;
-  TRACE_MARK(wave, 0);
 
   // the loads are issued first and fly while the block fills its lookup table
   Row<N> R;
@@ -704,7 +693,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
   const bool in_range = act >= 0 && act < G::P;
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
   const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
-  TRACE_MARK(wave, 1);
 
   // a3-a8
   float rew0, rew1;
@@ -716,14 +704,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
 
-  TRACE_MARK(wave, 3);
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
   if (a.obs) emit_obs<N>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
-  TRACE_MARK(wave, 4);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
   if (a.mask) emit_mask<N>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
 
-  TRACE_MARK(wave, 5);
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
     // Writing only the changed planes pays while state and outputs stay resident in the memory-side cache
@@ -737,7 +722,6 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_step_kernel(StepArgs a
     const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
   }
-  TRACE_MARK(wave, 6);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1256,13 +1240,6 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
   return PGXGO_OK;
 }
-
-#ifdef PGXGO_TRACE
-int pgxgo_debug_set_trace(unsigned long long* trace_dev) {
-  HIPCHK(hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &trace_dev, sizeof(trace_dev)));
-  return PGXGO_OK;
-}
-#endif
 
 int pgxgo_sync(pgxgo_t h) {
   if (!h) return PGXGO_EINVAL;
