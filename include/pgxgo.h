@@ -115,6 +115,23 @@ int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint
 int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev,
                   int32_t* actions_dev, float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev);
 
+/* Search-facing step (Sec. 5: tree search calls step from copies of earlier states).  The handle's `batch`
+ * environments are treated as a pool of state slots; for i in 0..n-1 (n <= batch):
+ *     state[dst_slots_dev[i]] = step(state[src_slots_dev[i]], actions_dev[i])
+ * with the semantics of pgxgo_step (action -1 = copy unchanged).  The source slot keeps its state unless it is
+ * also the destination of the same entry.  Outputs of entry i go to row i of the optional buffers
+ * mask_dev [n][mask_pitch], obs_dev [n][obs_pitch], rewards_dev [n][2], terminated_dev [n]; buffers bound with
+ * pgxgo_bind_outputs are not touched.  The environment index used for the seat draw on auto-reset is the
+ * destination slot.  The caller guarantees that destination slots are pairwise distinct and that no
+ * destination is the source of ANOTHER entry of the same call (the entries run concurrently).  A copied
+ * entry (action -1) reports zero rewards and the terminated flag of its state.  An entry with a slot index
+ * outside [0, batch) touches no state, reports terminated = 255 and gets zero-filled mask/observation rows. */
+int pgxgo_step_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* actions_dev, const int32_t* dst_slots_dev,
+                     uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev);
+
+/* state[dst_slots_dev[i]] = state[src_slots_dev[i]] for i in 0..n-1 (same constraints). */
+int pgxgo_copy_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* dst_slots_dev);
+
 /* Getters for the current state; each enqueues one kernel or copy into the caller's buffer. */
 int pgxgo_legal_mask(pgxgo_t h, uint8_t* dst_dev /* [batch][mask_pitch] */);
 int pgxgo_observe(pgxgo_t h, uint8_t* dst_dev /* [batch][obs_pitch] */);

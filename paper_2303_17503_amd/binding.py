@@ -38,6 +38,8 @@ def lib():
         L.pgxgo_random_actions.argtypes = [vp, u32, u32, vp, vp]
         L.pgxgo_step_sample.argtypes = [vp, vp, u32, u32, vp, vp]
         L.pgxgo_rollout.argtypes = [vp, i32, i32, u32, u32, vp, vp, vp, vp, vp, vp]
+        L.pgxgo_step_slots.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+        L.pgxgo_copy_slots.argtypes = [vp, i32, vp, vp]
         for n in ("legal_mask", "observe", "rewards", "terminated", "current_player"):
             getattr(L, "pgxgo_" + n).argtypes = [vp, vp]
         L.pgxgo_export_state.argtypes = [vp] * 11
@@ -158,6 +160,23 @@ class GoEnv:
         if start_t is not None: _need(start_t, torch.int32, (self.B,), "start_t")
         _check(lib().pgxgo_rollout(self._h, int(steps), S, seed & 0xFFFFFFFF, t0 & 0xFFFFFFFF, _ptr(start_t), _ptr(actions), _ptr(rewards),
                                    _ptr(terminated), _ptr(mask), _ptr(obs)), "pgxgo_rollout")
+
+    def step_slots(self, src, actions, dst, mask=None, obs=None, rewards=None, terminated=None):
+        """state[dst[i]] = step(state[src[i]], actions[i]); outputs of entry i in row i of the optional buffers."""
+        n = int(src.shape[0])
+        _need(src, torch.int32, (n,), "src"); _need(dst, torch.int32, (n,), "dst")
+        if actions is not None: _need(actions, torch.int32, (n,), "actions")
+        if mask is not None: _need(mask, torch.uint8, (n, self.mask_pitch), "mask")
+        if obs is not None: _need(obs, torch.uint8, (n, self.obs_pitch), "obs")
+        if rewards is not None: _need(rewards, torch.float32, (n, 2), "rewards")
+        if terminated is not None: _need(terminated, torch.uint8, (n,), "terminated")
+        _check(lib().pgxgo_step_slots(self._h, n, _ptr(src), _ptr(actions), _ptr(dst), _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)),
+               "pgxgo_step_slots")
+
+    def copy_slots(self, src, dst):
+        n = int(src.shape[0])
+        _need(src, torch.int32, (n,), "src"); _need(dst, torch.int32, (n,), "dst")
+        _check(lib().pgxgo_copy_slots(self._h, n, _ptr(src), _ptr(dst)), "pgxgo_copy_slots")
 
     def legal_mask(self, out=None):
         out = self.new_mask() if out is None else _need(out, torch.uint8, (self.B, self.mask_pitch), "mask")

@@ -155,7 +155,8 @@ __device__ __forceinline__ uint32_t flood_plain(uint32_t seed, uint32_t S) {
 // ------------------------------------------------------------------------------------------------
 template <int N>
 struct Lane {
-  int lane, j, r, b;     // lane id, board slot in the wavefront, row, global environment index
+  int lane, j, r, b;     // lane id, board slot in the wavefront, row, index of the board in the call (outputs, actions)
+  int slot;              // index of the environment whose state this board is (= b except in the slot kernels)
   bool valid;            // this lane holds a real row of a real board
   bool boardok;          // slot j holds a real board (also true for its sentinel lane)
   uint32_t seglo, seghi; // lanes of the rows of this lane's board
@@ -167,6 +168,7 @@ struct Lane {
     int rr = lane - j * G::STRIDE;
     r = rr - 1;
     b = wave * G::W + j;
+    slot = b;
     boardok = (j < G::W) && (b < B);
     valid = boardok && rr >= 1;
     uint64_t seg = (j < G::W) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
@@ -189,7 +191,7 @@ __device__ __forceinline__ void load_row(const uint4* __restrict__ planes, size_
 #pragma unroll
   for (int k = 0; k < G::NQ * 4 + 4; ++k) rec[k] = 0u;
   if (L.valid) {
-    const size_t idx = (size_t)L.b * N + L.r;
+    const size_t idx = (size_t)L.slot * N + L.r;
 #pragma unroll
     for (int k = 0; k < G::NQ; ++k) {
       uint4 v = planes[(size_t)k * rows_total + idx];
@@ -212,7 +214,7 @@ __device__ __forceinline__ void store_row(uint4* __restrict__ planes, size_t row
   for (int k = 0; k < G::HD; ++k) rec[k] = R.h[k];
   rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw;
   if (L.valid) {
-    const size_t idx = (size_t)L.b * N + L.r;
+    const size_t idx = (size_t)L.slot * N + L.r;
 #pragma unroll
     for (int k = 0; k < G::NQ; ++k) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
     uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
@@ -233,7 +235,7 @@ __device__ __forceinline__ void store_row_changed(uint4* __restrict__ planes, si
   rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw;
   old[G::HD] = Old.bk; old[G::HD + 1] = Old.wt; old[G::HD + 2] = Old.ab; old[G::HD + 3] = Old.aw;
   if (L.valid) {
-    const size_t idx = (size_t)L.b * N + L.r;
+    const size_t idx = (size_t)L.slot * N + L.r;
 #pragma unroll
     for (int k = 0; k < G::NQ; ++k) {
       const uint32_t diff = (rec[4 * k] ^ old[4 * k]) | (rec[4 * k + 1] ^ old[4 * k + 1]) | (rec[4 * k + 2] ^ old[4 * k + 2]) | (rec[4 * k + 3] ^ old[4 * k + 3]);
@@ -631,7 +633,7 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
       R.bk = R.wt = R.ab = R.aw = 0u;
       m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
       m.episode += 1;
-      m.bp = (int)(env_hash(cfg.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
+      m.bp = (int)(env_hash(cfg.seed, 1u, (uint32_t)L.slot, m.episode) & 1u);
     }
   }
   flag = ended || frozen;
@@ -722,6 +724,73 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
     const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// the slot kernel (tree search): entry i reads the state of slot src[i], applies actions[i] (all -1 when
+// actions is null: a plain copy) and writes the result to slot dst[i]; outputs go to row i.
+// ------------------------------------------------------------------------------------------------
+struct SlotArgs {
+  uint4* planes;
+  uint4* meta;
+  int pool;             // number of state slots (the handle's batch)
+  int n;                // entries of this call
+  const int32_t* src;
+  const int32_t* dst;
+  const int32_t* actions;
+  float* rew;           // [n][2] or null
+  uint8_t* term;        // [n] or null; 255 marks an entry whose slot index was out of range
+  uint8_t* mask;        // [n][mask_pitch] or null
+  uint8_t* obs;         // [n][obs_pitch] or null
+  int64_t mask_pitch, obs_pitch;
+  Rules rules;
+};
+
+template <int N>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(SlotArgs a) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
+  __shared__ uint2 lut[256];
+  const int wib = threadIdx.x >> 6;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  Lane<N> L(wave, threadIdx.x & 63, a.n);
+  const size_t rows_total = (size_t)a.pool * N;
+  const int src = L.boardok ? a.src[L.b] : 0, dst = L.boardok ? a.dst[L.b] : 0;
+  const bool in_pool = src >= 0 && src < a.pool && dst >= 0 && dst < a.pool;
+  const bool bad = L.boardok && !in_pool;
+  if (bad) { L.boardok = false; L.valid = false; L.full = 0u; }   // the entry becomes inert: no state access, no outputs
+  L.slot = src;
+  Row<N> R;
+  load_row<N>(a.planes, rows_total, L, R);
+  const uint4 meta_raw = L.boardok ? a.meta[src] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
+  const int act = (L.boardok && a.actions) ? a.actions[L.b] : -1;
+  fill_spread_table(lut);
+  if (wave * G::W >= a.n) return;
+  Meta m = unpack_meta(meta_raw);
+  L.slot = dst;   // from here on the board is environment dst (seat draw on reset, state store)
+
+  const bool skip = !L.boardok || act == -1;
+  const bool in_range = act >= 0 && act < G::P;
+  const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
+  const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
+  float rew0, rew1;
+  bool flag, reset;
+  uint32_t captured;
+  apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
+  if ((threadIdx.x & 63) == L.j * G::STRIDE + 1 && L.j < G::W && L.b < a.n) {   // row-0 lane of the entry, inert or not
+    if (bad) { if (a.term) a.term[L.b] = 255; }
+    else {
+      // a copied entry (action -1) reports what a skipped step reports for a fresh handle: no reward, and its terminated state
+      if (a.rew) *(float2*)(a.rew + 2 * (size_t)L.b) = skip ? make_float2(0.f, 0.f) : make_float2(rew0, rew1);
+      if (a.term) a.term[L.b] = (uint8_t)(skip ? m.term : (flag ? 1 : 0));
+    }
+  }
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  if (a.obs) emit_obs<N>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  if (a.mask) emit_mask<N>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  store_row<N>(a.planes, rows_total, L, R);
+  if (L.valid && L.r == 0) a.meta[dst] = pack_meta(m);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1063,6 +1132,13 @@ int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
 }
 
 template <int N>
+int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
+  hipLaunchKernelGGL(go_step_slots_kernel<N>, dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
 int launch_export(pgxgo_ctx* h, const CanonArgs& c) {
   hipLaunchKernelGGL(go_export_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, c);
   HIPCHK(hipGetLastError());
@@ -1182,6 +1258,21 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
   a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
   return DISPATCH_N(h, launch_rollout<19>(h, a), launch_rollout<9>(h, a));
+}
+
+int pgxgo_step_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* actions_dev, const int32_t* dst_slots_dev,
+                     uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
+  if (!h || n < 0 || n > h->B || !src_slots_dev || !dst_slots_dev) return PGXGO_EINVAL;
+  if (n == 0) return PGXGO_OK;
+  SlotArgs a;
+  a.planes = h->planes; a.meta = h->meta; a.pool = h->B; a.n = n; a.src = src_slots_dev; a.dst = dst_slots_dev; a.actions = actions_dev;
+  a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
+  a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
+  return DISPATCH_N(h, launch_slots<19>(h, a), launch_slots<9>(h, a));
+}
+
+int pgxgo_copy_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* dst_slots_dev) {
+  return pgxgo_step_slots(h, n, src_slots_dev, nullptr, dst_slots_dev, nullptr, nullptr, nullptr, nullptr);
 }
 
 int pgxgo_random_actions(pgxgo_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev) {

@@ -329,3 +329,77 @@ def test_rollout_single_slice_with_staggered_start_at_full_batch():
     g = env.export_state()
     assert (g["board"].index_select(0, sel).cpu().numpy() == orc.export_state().board).all()
     assert int(g["episode"].max()) >= 1
+
+
+@pytest.mark.parametrize("N,pool,auto_reset", [(9, 40, False), (19, 25, True)])
+def test_slot_step_and_copy_for_tree_search(N, pool, auto_reset):
+    """step_slots / copy_slots against the oracle: a pool of states, random (src -> dst) expansions with random
+    legal or illegal actions, like a search expanding children from stored nodes."""
+    import paper_2303_17503_amd as pg
+    from gpu_common import to_np
+    rng = np.random.default_rng(N)
+    seed, P = 31, N * N
+    env = pg.GoEnv(pool, N, seed=seed, auto_reset=auto_reset)
+    orc = oracle.GoOracle(pool, N, seed=seed, auto_reset=auto_reset)
+    for t in range(30):                      # some history in every slot
+        a = orc.random_actions(seed, t)
+        env.step(torch.as_tensor(a, device="cuda")); orc.step(a)
+    fields = ("board", "history", "ko", "to_play", "steps", "passes", "terminated", "black_player", "episode")
+
+    def check_pool(tag):
+        g, c = env.export_state(), orc.export_state()
+        for name in fields:
+            assert (to_np(g[name]).astype(np.int64) == getattr(c, name).astype(np.int64)).all(), (tag, name)
+        assert (to_np(env.legal_mask()) == orc.legal_mask()).all(), tag
+
+    check_pool("start")
+    for it in range(40):
+        n = int(rng.integers(1, pool // 2))
+        perm = rng.permutation(pool)
+        dst = perm[:n].astype(np.int32)                       # distinct destinations
+        free_src = perm[n:]                                   # sources that are nobody's destination ...
+        src = rng.choice(free_src, n).astype(np.int32)
+        same = rng.random(n) < 0.3                            # ... or the entry's own destination (in-place step)
+        src = np.where(same, dst, src).astype(np.int32)
+        st = orc.export_state()
+        tmp = oracle.GoOracle(n, N, seed=seed, auto_reset=auto_reset, env_ids=dst)
+        sub = oracle.State(n, P)
+        for name in fields:
+            getattr(sub, name)[...] = getattr(st, name)[src]
+        tmp.import_state(sub)
+        m = tmp.legal_mask()
+        act = np.array([rng.choice(np.flatnonzero(m[i])) for i in range(n)], np.int32)
+        kind = rng.integers(0, 10, n)
+        act = np.where(kind == 0, rng.integers(0, P, n), act)  # maybe illegal
+        act = np.where(kind == 1, -1, act).astype(np.int32)    # plain copy
+        tmp.step(act)
+        mask = torch.full((n, P + 1), 9, dtype=torch.uint8, device="cuda")
+        obs = torch.full((n, P * 17), 9, dtype=torch.uint8, device="cuda")
+        rew = torch.full((n, 2), 9.0, dtype=torch.float32, device="cuda")
+        term = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+        env.step_slots(torch.as_tensor(src, device="cuda"), torch.as_tensor(act, device="cuda"), torch.as_tensor(dst, device="cuda"),
+                       mask=mask, obs=obs, rewards=rew, terminated=term)
+        assert (to_np(mask) == tmp.legal_mask()).all(), it
+        assert (to_np(obs).reshape(n, N, N, 17) == tmp.observe()).all(), it
+        copied = act == -1
+        assert (to_np(rew)[~copied] == tmp.rewards()[~copied]).all() and (to_np(rew)[copied] == 0).all(), it
+        assert (to_np(term)[~copied] == tmp.terminated()[~copied]).all(), it
+        assert (to_np(term)[copied] == sub.terminated[copied]).all(), it
+        after = tmp.export_state()
+        for name in fields:
+            getattr(st, name)[dst] = getattr(after, name)
+        orc.import_state(st)
+        check_pool(f"iteration {it}")
+    # copy_slots, and an out-of-range entry
+    src = np.array([0, 1, 2], np.int32); dst = np.array([5, 6, 7], np.int32)
+    env.copy_slots(torch.as_tensor(src, device="cuda"), torch.as_tensor(dst, device="cuda"))
+    st = orc.export_state()
+    for name in fields:
+        getattr(st, name)[dst] = getattr(st, name)[src]
+    orc.import_state(st)
+    check_pool("copy")
+    term = torch.zeros(2, dtype=torch.uint8, device="cuda")
+    env.step_slots(torch.as_tensor(np.array([3, pool + 5], np.int32), device="cuda"), torch.as_tensor(np.array([-1, 0], np.int32), device="cuda"),
+                   torch.as_tensor(np.array([3, 4], np.int32), device="cuda"), terminated=term)
+    assert to_np(term)[1] == 255
+    check_pool("bad slot ignored")
