@@ -11,19 +11,24 @@
 //     wave shift moves every row to its north/south neighbour and brings zeros in from off the board.
 //   * Stones are row bitboards (bit c = column c).  East/west neighbours are register shifts, north/south
 //     neighbours are DPP shifts; a flood-fill step is a handful of VALU instructions for all W boards at once.
-//   * Facts about a whole board (a move is legal, a chain has one liberty, ...) are kept as 64-bit lane
-//     masks in scalar registers: a ballot, a few scalar AND/popcount per board with compile-time segment
-//     masks, and the mask is used directly as the select condition of the next vector instruction.
+//   * Facts about a whole board (a move is legal, a chain has one liberty, ...) come from a ballot masked with
+//     the lane segment of the board; every lane of the board then holds the same answer.
 //   * The state keeps, besides the stones, the set of stones whose chain has exactly one liberty
 //     ("atari sets").  With them captures, the ko test and the whole legal mask are stencils; only the
 //     chains touched by the move are re-flooded (the merged chain and at most four opposing neighbours),
-//     and a flood stops as soon as two liberties have been seen.
+//     a flood stops as soon as two liberties have been seen, and several growth steps are taken per
+//     (comparatively expensive) look at the liberties.
 //   * History is stored point-major: 16 bits per point = 8 plies x (black, white), two points per dword,
 //     so a ply is one shift-and-insert per dword and the [N][N][17] byte observation is produced by
 //     building the 17-bit-per-point bit stream of a board in LDS and expanding 16 bits -> 16 bytes per
-//     lane with a multiply-mask, stored as aligned 16-byte vectors.
+//     lane through a 256-entry LDS table, stored as aligned 16-byte vectors.
 //   * HBM layout: struct of arrays of 16-byte vectors, plane k holds dwords 4k..4k+3 of every row record,
 //     indexed [env*N + row], so every load/store instruction of a wavefront touches one contiguous run.
+//     Only the planes of a row that changed are written back (absolute colours make unchanged points
+//     keep their history word).
+//   * Kernels: go_step_kernel (one ply per launch, optionally drawing the next random action),
+//     go_rollout_kernel (T plies per launch, state in registers), go_step_slots_kernel (tree search: step
+//     from and to arbitrary state slots), plus small set-up / export / import kernels.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
