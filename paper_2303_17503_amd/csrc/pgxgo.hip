@@ -286,22 +286,27 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
   __syncthreads();
 }
 
-template <int NBYTES, int ROUNDS>
-__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, int lane) {
+template <int ROUNDS>
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
   uint8_t* base = dst - head;
-  const uint32_t total = head + NBYTES;
-  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1; m1 - m0 <= NBYTES/16 <= 64*ROUNDS
+  const uint32_t total = head + nbytes;
+  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1, at most 64*ROUNDS of them
   const uint32_t mine = m0 + (uint32_t)lane;             // this lane's group in round 0; round i adds 64*i
   const uint16_t* src = (const uint16_t*)bits + mine;
   uint4* out = (uint4*)base + mine;
-  uint32_t v[ROUNDS];
+  constexpr int GROUP = 6;   // rounds in flight at a time (bounds the registers held by pending LDS reads)
 #pragma unroll
-  for (int i = 0; i < ROUNDS; ++i) v[i] = (i + 1 < ROUNDS || mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+  for (int g = 0; g < ROUNDS; g += GROUP) {
+    uint32_t v[GROUP];
 #pragma unroll
-  for (int i = 0; i < ROUNDS; ++i) {
-    const uint2 lo = lut[v[i] & 255u], hi = lut[v[i] >> 8];
-    if (i + 1 < ROUNDS || mine + 64u * i < m1) out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = (mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+#pragma unroll
+    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
+      const uint2 lo = lut[v[i - g] & 255u], hi = lut[v[i - g] >> 8];
+      if (mine + 64u * i < m1) out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
   if (lane < 32) {
     uint32_t i = lane & 15u, pos;
@@ -312,27 +317,35 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   }
 }
 
-// Legal mask bytes [N*N+1] of every board of the wavefront.
+// Legal mask bytes [N*N+1] of every board of the wavefront.  With the tight pitch the boards of a wavefront are
+// one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
 template <int N>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
                                           uint32_t* lds_mask, const uint2* lut) {
   using G = Geo<N>;
-  if (L.lane < G::W * G::MASK_DW) lds_mask[L.lane] = 0u;
-  static_assert(G::W * G::MASK_DW <= 64, "mask staging is cleared by one store per lane");
+  static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
+  const bool tight = mask_pitch == G::A;
+  const int b0 = wave * G::W;
+  const int nb = B - b0 < G::W ? B - b0 : G::W;   // boards of this wavefront
+  lds_mask[L.lane] = 0u;
   wave_lds_fence();
   if (L.valid) {
-    uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u);
-    uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
-    uint32_t* reg = lds_mask + L.j * G::MASK_DW;
+    uint32_t* reg;
+    uint32_t head;
+    if (tight) { head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * G::A) & 15u) + (uint32_t)(L.j * G::A); reg = lds_mask; }
+    else { head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u); reg = lds_mask + L.j * G::MASK_DW; }
+    const uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
     atomicOr(&reg[q], legal << s);
     if (s + N > 32u) atomicOr(&reg[q + 1], legal >> (32u - s));
-    if (L.r == 0) { uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
+    if (L.r == 0) { const uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
   }
   wave_lds_fence();
+  if (tight) {
+    emit_bytes<(G::W * G::A / 16 + 63) / 64>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane);
+  } else {
 #pragma unroll
-  for (int jj = 0; jj < G::W; ++jj) {
-    const int bb = wave * G::W + jj;
-    if (bb < B) emit_bytes<G::A, G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)bb * mask_pitch, L.lane);
+    for (int jj = 0; jj < G::W; ++jj)
+      if (jj < nb) emit_bytes<G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
   }
   wave_lds_fence();
 }
@@ -342,6 +355,10 @@ template <int N>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
                                          int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut) {
   using G = Geo<N>;
+  static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
+  const bool tight = obs_pitch == G::OBS;
+  const int b0 = wave * G::W;
+  const int nb = B - b0 < G::W ? B - b0 : G::W;
   // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
   // then the colour bit (Appendix C "Go", Observation); a row is N such pieces back to back.
   uint32_t S[G::NR];
@@ -370,9 +387,12 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   }
   wave_lds_fence();
   if (L.valid) {
-    uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u);
-    uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
-    uint32_t* reg = lds_obs + L.j * G::OBS_DW + q;
+    uint32_t* reg;
+    uint32_t head;
+    if (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * G::OBS) & 15u) + (uint32_t)(L.j * G::OBS); reg = lds_obs; }
+    else { head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u); reg = lds_obs + L.j * G::OBS_DW; }
+    const uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
+    reg += q;
     // shifted string T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door
     atomicOr(&reg[0], S[0] << s);
 #pragma unroll
@@ -384,10 +404,12 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
     }
   }
   wave_lds_fence();
+  if (tight) {
+    emit_bytes<(G::W * G::OBS / 16 + 63) / 64>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane);
+  } else {
 #pragma unroll
-  for (int jj = 0; jj < G::W; ++jj) {
-    const int bb = wave * G::W + jj;
-    if (bb < B) emit_bytes<G::OBS, G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)bb * obs_pitch, L.lane);
+    for (int jj = 0; jj < G::W; ++jj)
+      if (jj < nb) emit_bytes<G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
   }
   wave_lds_fence();
 }
