@@ -319,12 +319,12 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
 
 // Legal mask bytes [N*N+1] of every board of the wavefront.  With the tight pitch the boards of a wavefront are
 // one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
-template <int N>
+template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
                                           uint32_t* lds_mask, const uint2* lut) {
   using G = Geo<N>;
   static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
-  const bool tight = mask_pitch == G::A;
+  constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1
   const int b0 = wave * G::W;
   const int nb = B - b0 < G::W ? B - b0 : G::W;   // boards of this wavefront
   lds_mask[L.lane] = 0u;
@@ -332,7 +332,7 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   if (L.valid) {
     uint32_t* reg;
     uint32_t head;
-    if (tight) { head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * G::A) & 15u) + (uint32_t)(L.j * G::A); reg = lds_mask; }
+    if constexpr (tight) { head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * G::A) & 15u) + (uint32_t)(L.j * G::A); reg = lds_mask; }
     else { head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u); reg = lds_mask + L.j * G::MASK_DW; }
     const uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
     atomicOr(&reg[q], legal << s);
@@ -340,7 +340,7 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
     if (L.r == 0) { const uint32_t o2 = head + G::P; atomicOr(&reg[o2 >> 5], 1u << (o2 & 31u)); }   // pass is always legal
   }
   wave_lds_fence();
-  if (tight) {
+  if constexpr (tight) {
     emit_bytes<(G::W * G::A / 16 + 63) / 64>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane);
   } else {
 #pragma unroll
@@ -351,12 +351,12 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
 }
 
 // Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
-template <int N>
+template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
                                          int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut) {
   using G = Geo<N>;
   static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
-  const bool tight = obs_pitch == G::OBS;
+  constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17
   const int b0 = wave * G::W;
   const int nb = B - b0 < G::W ? B - b0 : G::W;
   // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
@@ -389,7 +389,7 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   if (L.valid) {
     uint32_t* reg;
     uint32_t head;
-    if (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * G::OBS) & 15u) + (uint32_t)(L.j * G::OBS); reg = lds_obs; }
+    if constexpr (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * G::OBS) & 15u) + (uint32_t)(L.j * G::OBS); reg = lds_obs; }
     else { head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u); reg = lds_obs + L.j * G::OBS_DW; }
     const uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
     reg += q;
@@ -404,7 +404,7 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
     }
   }
   wave_lds_fence();
-  if (tight) {
+  if constexpr (tight) {
     emit_bytes<(G::W * G::OBS / 16 + 63) / 64>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane);
   } else {
 #pragma unroll
@@ -414,12 +414,12 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   wave_lds_fence();
 }
 
-template <int N>
+template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
                                              uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut) {
-  if (mask) emit_mask<N>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut);
-  if (obs) emit_obs<N>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut);
+  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut);
+  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -696,7 +696,7 @@ struct StepArgs {
   int32_t* next_actions;
 };
 
-template <int N, bool SAMPLE>
+template <int N, bool SAMPLE, bool TIGHT>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -734,9 +734,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   }
 
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
-  if (a.obs) emit_obs<N>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
@@ -773,7 +773,7 @@ struct SlotArgs {
   Rules rules;
 };
 
-template <int N>
+template <int N, bool TIGHT>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(SlotArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -814,8 +814,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(S
     }
   }
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.obs) emit_obs<N>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
-  if (a.mask) emit_mask<N>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
   store_row<N>(a.planes, rows_total, L, R);
   if (L.valid && L.r == 0) a.meta[dst] = pack_meta(m);
 }
@@ -841,7 +841,7 @@ struct RolloutArgs {
   int64_t mask_pitch, obs_pitch;
 };
 
-template <int N>
+template <int N, bool TIGHT>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(RolloutArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -877,7 +877,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
       if (a.rew) *(float2*)(a.rew + 2 * e) = skip ? make_float2(0.f, 0.f) : make_float2(rew0, rew1);
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
-    emit_outputs<N>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
+    emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
                     a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
@@ -889,7 +889,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
 // ------------------------------------------------------------------------------------------------
 // auxiliary kernels
 // ------------------------------------------------------------------------------------------------
-template <int N>
+template <int N, bool TIGHT>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint4* planes, const uint4* meta, int B, uint8_t* mask,
                                                                       int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch) {
   using G = Geo<N>;
@@ -905,7 +905,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint
   load_row<N>(planes, (size_t)B * N, L, R);
   Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  emit_outputs<N>(L, R, legal, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
+  emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
 }
 
 // k-th legal action of the current position, same row-per-lane mapping as the step kernel
@@ -1118,10 +1118,18 @@ unsigned waves_for(int B) { return (unsigned)((B + Geo<N>::W - 1) / Geo<N>::W); 
 template <int N>
 unsigned blocks_for(int B) { return (waves_for<N>(B) + kWavesPerBlock - 1) / kWavesPerBlock; }
 
+// both output pitches are the tight ones: the kernels may treat a wavefront's boards as one run of bytes
+template <int N>
+bool tight_pitches(const pgxgo_ctx* h) { return h->mask_pitch == Geo<N>::A && h->obs_pitch == Geo<N>::OBS; }
+
 template <int N>
 int launch_emit(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {
-  hipLaunchKernelGGL(go_emit_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
-                     h->mask_pitch, obs, h->obs_pitch);
+  if (tight_pitches<N>(h))
+    hipLaunchKernelGGL((go_emit_kernel<N, true>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
+                       h->mask_pitch, obs, h->obs_pitch);
+  else
+    hipLaunchKernelGGL((go_emit_kernel<N, false>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
+                       h->mask_pitch, obs, h->obs_pitch);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1137,8 +1145,11 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
   const dim3 grid(blocks_for<N>(h->B)), block(64 * kWavesPerBlock);
-  if (sample) hipLaunchKernelGGL((go_step_kernel<N, true>), grid, block, 0, h->stream, a);
-  else hipLaunchKernelGGL((go_step_kernel<N, false>), grid, block, 0, h->stream, a);
+  const bool tight = tight_pitches<N>(h);
+  if (sample && tight) hipLaunchKernelGGL((go_step_kernel<N, true, true>), grid, block, 0, h->stream, a);
+  else if (sample) hipLaunchKernelGGL((go_step_kernel<N, true, false>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_step_kernel<N, false, true>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_kernel<N, false, false>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1153,14 +1164,16 @@ int launch_random(pgxgo_ctx* h, uint32_t seed, uint32_t t, const int32_t* start_
 
 template <int N>
 int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
-  hipLaunchKernelGGL(go_rollout_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_rollout_kernel<N, true>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  else hipLaunchKernelGGL((go_rollout_kernel<N, false>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
 
 template <int N>
 int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
-  hipLaunchKernelGGL(go_step_slots_kernel<N>, dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_step_slots_kernel<N, true>), dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_slots_kernel<N, false>), dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
