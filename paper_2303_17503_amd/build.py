@@ -1,10 +1,10 @@
-"""Compile the HIP library for gfx950 into paper_2303_17503_amd/libpgxgo.so (in-tree)."""
+"""Compile the HIP library (Go and Hex kernels) for gfx950 into paper_2303_17503_amd/libpgxgo.so (in-tree)."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "pgxgo.hip")
+SRCS = [os.path.join(HERE, "csrc", "pgxgo.hip"), os.path.join(HERE, "csrc", "pgxhex.hip")]
 LIB = os.path.join(HERE, "libpgxgo.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -14,7 +14,7 @@ def build(verbose: bool = False) -> str:
         HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-command-line-argument",
-        "-I", os.path.join(ROOT, "include"), "-o", LIB, SRC,
+        "-I", os.path.join(ROOT, "include"), "-o", LIB, *SRCS,
     ]
     if verbose:
         print(" ".join(cmd))

@@ -1,0 +1,589 @@
+// pgxhex.hip -- batched Hex environment step for AMD MI355X (gfx950, wave64), C ABI in include/pgxhex.h.
+//
+// What is computed: the Hex environment of the Pgx paper (arXiv 2303.17503): Fig. 2 (init/step API,
+// legal_action_mask, observation, current_player), Table 1 (11x11x4 observation, 122 actions), Appendix C "Hex"
+// (stones placed in turn, a player wins by joining their two sides, swap rule on the second turn, planes =
+// mover's stones / opponent's stones / colour / swap-is-legal, rewards +1/-1), Sec. 4.1 (random policy,
+// auto-reset on termination).
+//
+// Mapping (the same as the Go kernels of this library): one board row per lane, 5 boards per wavefront, board j
+// in lanes 12j+1 .. 12j+11 with all-zero sentinel lanes between boards.  A row is one dword (black in bits 0-10,
+// white in bits 16-26), so a board is 44 bytes of state plus one 16-byte scalar record.  The six neighbours of a
+// cell are two register shifts plus the two DPP row shifts and their one-column offsets; the winner test floods
+// the mover's stones from the stone just placed and asks by ballot whether the flood touches both of the mover's
+// sides.  Mask and observation bytes are staged as a bit stream in LDS (4 bits per cell for the observation) and
+// written as aligned 16-byte vectors; the boards of a wavefront form one contiguous run of bytes.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "pgxhex.h"
+#include "wave_common.hpp"
+
+namespace {
+
+using namespace pgxwave;
+
+thread_local int g_last_hip = 0;
+
+#define HIPCHK(expr)                                   \
+  do {                                                 \
+    hipError_t e_ = (expr);                            \
+    if (e_ != hipSuccess) {                            \
+      g_last_hip = (int)e_;                            \
+      return PGXHEX_EHIP;                              \
+    }                                                  \
+  } while (0)
+
+constexpr int N = PGXHEX_N;
+constexpr int P = N * N;
+constexpr int A = P + 1;                    // Table 1: 122 actions
+constexpr int OBS = P * 4;                  // Table 1: 11 x 11 x 4
+constexpr int STRIDE = N + 1;               // lanes per board, one of them the zero sentinel row
+constexpr int W = 63 / STRIDE;              // boards per wavefront
+constexpr uint32_t FULL = (1u << N) - 1u;
+constexpr int kWavesPerBlock = 4;           // wavefronts never synchronise with each other after the table is filled
+constexpr int OBS_DW = ((15 + W * OBS + 31) / 32 + 3) / 4 * 4;   // LDS dwords of a wavefront's observation bit stream
+constexpr int MASK_DW = 64;                                      // the mask stream is cleared by one store per lane
+constexpr int OBS_ROUNDS = (W * OBS / 16 + 63) / 64;
+constexpr int MASK_ROUNDS = (W * A / 16 + 63) / 64;
+static_assert(A == PGXHEX_ACTIONS && OBS == PGXHEX_OBS_BYTES, "header constants");
+static_assert((15 + W * A + 31) / 32 <= MASK_DW, "mask stream fits its staging area");
+static_assert(N <= 16, "a row holds both colours in one dword");
+
+// per-board scalars, one 16-byte record: x = steps[0:8) | white_to_move[8] | terminated[9] | black_player[10],
+// y = episode, z = illegal actions received
+struct Meta {
+  int steps, wtm, term, bp;
+  uint32_t episode, illegal;
+};
+__device__ __forceinline__ Meta unpack_meta(uint4 v) {
+  Meta m;
+  m.steps = v.x & 0xFF; m.wtm = (v.x >> 8) & 1; m.term = (v.x >> 9) & 1; m.bp = (v.x >> 10) & 1;
+  m.episode = v.y; m.illegal = v.z;
+  return m;
+}
+__device__ __forceinline__ uint4 pack_meta(const Meta& m) {
+  return make_uint4((uint32_t)m.steps | ((uint32_t)m.wtm << 8) | ((uint32_t)m.term << 9) | ((uint32_t)m.bp << 10), m.episode, m.illegal, 0u);
+}
+
+struct Lane {
+  int lane, j, r, b;     // lane id, board slot in the wavefront, row, environment index
+  bool valid;            // this lane holds a real row of a real board
+  bool boardok;          // slot j holds a real board (also true for its sentinel lane)
+  uint32_t seglo, seghi; // lanes of the rows of this lane's board
+  uint32_t full;
+  __device__ __forceinline__ Lane(int wave, int lane_, int B) {
+    lane = lane_;
+    j = lane / STRIDE;
+    const int rr = lane - j * STRIDE;
+    r = rr - 1;
+    b = wave * W + j;
+    boardok = (j < W) && (b < B);
+    valid = boardok && rr >= 1;
+    const uint64_t seg = (j < W) ? (((1ull << N) - 1ull) << (j * STRIDE + 1)) : 0ull;
+    seglo = (uint32_t)seg; seghi = (uint32_t)(seg >> 32);
+    full = valid ? FULL : 0u;
+  }
+};
+
+// all cells touching the set x (Appendix C "Hex"; reading: (r,c) touches (r,c-1) (r,c+1) (r-1,c) (r-1,c+1) (r+1,c)
+// (r+1,c-1)).  Bits beyond column N-1 may be set; callers intersect with on-board sets.
+__device__ __forceinline__ uint32_t hex_dilate(uint32_t x) {
+  const uint32_t up = from_lane_below(x), down = from_lane_above(x);   // rows r-1 and r+1
+  return (x << 1) | (x >> 1) | up | (up >> 1) | down | (down << 1);
+}
+
+// bit i of x (x < 256) -> bit 4i
+__device__ __forceinline__ uint32_t spread_every4(uint32_t x) {
+  x = (x | (x << 12)) & 0x000F000Fu;
+  x = (x | (x << 6)) & 0x03030303u;
+  x = (x | (x << 3)) & 0x11111111u;
+  return x;
+}
+
+// Legal mask [122] and observation [11][11][4] bytes of every board of the wavefront (Fig. 2, Table 1, Appendix C
+// "Hex" Observation / Action) from the position after the ply.
+__device__ __forceinline__ void emit_outputs(const Lane& L, uint32_t bk, uint32_t wt, const Meta& m, int wave, int B, uint8_t* mask, uint8_t* obs,
+                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut) {
+  const int b0 = wave * W;
+  const int nb = B - b0 < W ? B - b0 : W;
+  const uint32_t E = L.full & ~(bk | wt);
+  const bool swap = m.steps == 1;   // the swap is on offer on the second turn only
+  if (mask) {
+    lds_mask[L.lane] = 0u;
+    wave_lds_fence();
+    if (L.valid) {
+      const uint32_t head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * A) & 15u) + (uint32_t)(L.j * A);
+      const uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
+      atomicOr(&lds_mask[q], E << s);
+      if (s + N > 32u) atomicOr(&lds_mask[q + 1], E >> (32u - s));
+      if (L.r == 0 && swap) { const uint32_t o2 = head + P; atomicOr(&lds_mask[o2 >> 5], 1u << (o2 & 31u)); }
+    }
+    wave_lds_fence();
+    emit_bytes<MASK_ROUNDS>(lds_mask, lut, mask + (int64_t)b0 * A, (uint32_t)(nb * A), L.lane);
+    wave_lds_fence();
+  }
+  if (obs) {
+    // 4 bits per cell: mover's stone, opponent's stone, Black to move, swap legal; a row is N such nibbles
+    const uint32_t mine = m.wtm ? wt : bk, theirs = m.wtm ? bk : wt;
+    const uint32_t flags = (m.wtm ? 0u : 0x44444444u) | (swap ? 0x88888888u : 0u);
+    const uint32_t lo = spread_every4(mine & 255u) | (spread_every4(theirs & 255u) << 1) | (L.valid ? flags : 0u);
+    const uint32_t hi = (spread_every4(mine >> 8) | (spread_every4(theirs >> 8) << 1) | (L.valid ? flags : 0u)) & ((1u << (4 * (N - 8))) - 1u);
+    if (L.lane < OBS_DW / 4) ((uint4*)lds_obs)[L.lane] = make_uint4(0u, 0u, 0u, 0u);
+    wave_lds_fence();
+    if (L.valid) {
+      const uint32_t head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * OBS) & 15u) + (uint32_t)(L.j * OBS);
+      const uint32_t o = head + (uint32_t)(4 * N * L.r), q = o >> 5, s = o & 31u;
+      atomicOr(&lds_obs[q], lo << s);
+      atomicOr(&lds_obs[q + 1], __funnelshift_l(lo, hi, s));
+      const uint32_t t2 = __funnelshift_l(hi, 0u, s);
+      if (t2) atomicOr(&lds_obs[q + 2], t2);
+    }
+    wave_lds_fence();
+    emit_bytes<OBS_ROUNDS>(lds_obs, lut, obs + (int64_t)b0 * OBS, (uint32_t)(nb * OBS), L.lane);
+    wave_lds_fence();
+  }
+}
+
+// Uniform random legal action (Sec. 4.1): the k-th legal action in ascending order, k = hash mod legal_count; the
+// swap, when legal, is the last one; 0 when nothing is legal; -1 while the environment waits for its start time.
+__device__ __forceinline__ int draw_action(const Lane& L, uint32_t E, bool swap, uint32_t seed, uint32_t t, bool wait) {
+  const uint32_t cnt = __popc(E);
+  uint32_t before = 0u, total = swap ? 1u : 0u;
+#pragma unroll
+  for (int k = 0; (1 << k) <= N; ++k) {
+    const uint64_t m = __ballot((cnt >> k) & 1u);
+    const uint32_t lo = (uint32_t)m & L.seglo, hi = (uint32_t)(m >> 32) & L.seghi;
+    before += __builtin_amdgcn_mbcnt_hi(hi, __builtin_amdgcn_mbcnt_lo(lo, 0u)) << k;
+    total += (uint32_t)(__popc(lo) + __popc(hi)) << k;
+  }
+  const uint32_t k = env_hash(seed, 0u, (uint32_t)L.b, t) % (total ? total : 1u);
+  uint32_t n = k - before, w = E, pos = 0u;   // position of the (n+1)-th set bit of the row word by halving
+#pragma unroll
+  for (int width = 8; width >= 1; width >>= 1) {
+    const uint32_t c = __popc(w & ((1u << width) - 1u));
+    if (n >= c) { n -= c; w >>= width; pos += width; }
+  }
+  const bool mine = L.valid && k >= before && k < before + cnt;
+  const uint64_t sel = __ballot(mine);
+  const uint32_t slo = (uint32_t)sel & L.seglo, shi = (uint32_t)(sel >> 32) & L.seghi;
+  const int src = slo ? __ffs(slo) - 1 : (shi ? 31 + __ffs(shi) : 0);
+  const int pr = src - (L.j * STRIDE + 1);
+  const int pc = __shfl((int)pos, src);
+  if (wait) return -1;
+  if (total == 0u) return 0;
+  if (swap && k == total - 1u) return P;
+  return pr * N + pc;
+}
+
+struct StepArgs {
+  uint32_t* rows;            // [B][N] row words
+  uint4* meta;               // [B]
+  const int32_t* actions;    // [B]
+  float* rew;                // [B][2]
+  uint8_t* term;             // [B]
+  uint8_t* mask;             // [B][A] or null
+  uint8_t* obs;              // [B][OBS] or null
+  int B;
+  uint32_t seed;
+  int auto_reset;
+  uint32_t sample_seed, sample_t;
+  const int32_t* start_t;    // nullable
+  int32_t* next_actions;     // SAMPLE only
+};
+
+// One ply of every game (Fig. 2 "step"): a1 decode, a2 legality gate, a3 placement or swap, a4 winner test,
+// a5 rewards / termination / auto-reset, a6 legal mask, a7 observation, a8 state store, optionally the next draw.
+template <bool SAMPLE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
+  __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const Lane L(wave, lane, a.B);
+  const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
+  const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
+  const int act = L.boardok ? a.actions[L.b] : -1;
+  fill_spread_table(lut);
+  if (wave * W >= a.B) return;
+
+  uint32_t bk = word & 0xFFFFu, wt = word >> 16;
+  Meta m = unpack_meta(mv);
+  const bool skip = act == -1 || !L.boardok;
+  const bool frozen = !skip && m.term;        // finished earlier and not reset: nothing changes
+  const bool live = !skip && !frozen;
+  const uint32_t E = L.full & ~(bk | wt);
+  const bool want_point = live && act >= 0 && act < P;
+  const int pr = want_point ? act / N : -100;
+  const int pc = want_point ? act - pr * N : 0;
+  const uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
+  const bool point_ok = want_point && board_any((E & pbit) != 0u, L.seglo, L.seghi);
+  const bool swap_ok = live && act == P && m.steps == 1;
+  const bool illegal_now = live && !point_ok && !swap_ok;
+  const bool moved = point_ok || swap_ok;
+  const int wtm = m.wtm;
+
+  // swap rule: on the second turn the board holds Black's lone stone (r0,c0); it comes off and a white stone goes to (c0,r0)
+  const uint64_t nz = __ballot(bk != 0u);
+  const uint32_t zlo = (uint32_t)nz & L.seglo, zhi = (uint32_t)(nz >> 32) & L.seghi;
+  const int src = zlo ? __ffs(zlo) - 1 : (zhi ? 31 + __ffs(zhi) : 0);
+  const int r0 = src - (L.j * STRIDE + 1);
+  const int c0 = __ffs(__shfl((int)bk, src)) - 1;
+  const uint32_t swapped = (L.valid && L.r == c0 && r0 >= 0) ? (1u << (r0 & 15)) : 0u;
+  const uint32_t placed = swap_ok ? swapped : (point_ok ? pbit : 0u);
+  if (swap_ok) { bk = 0u; wt = swapped; }
+  else if (wtm) wt |= placed;
+  else bk |= placed;
+
+  // winner test: the chain of the new stone must touch both of the mover's sides
+  const uint32_t S = wtm ? wt : bk;
+  uint32_t F = placed;
+  for (;;) {
+    F |= hex_dilate(F) & S;
+    F |= hex_dilate(F) & S;
+    const uint32_t G = F | (hex_dilate(F) & S);
+    const bool ch = G != F;
+    F = G;
+    if (__ballot(ch) == 0ull) break;
+  }
+  const bool side_a = wtm ? (F & 1u) != 0u : (F != 0u && L.r == 0);
+  const bool side_b = wtm ? ((F >> (N - 1)) & 1u) != 0u : (F != 0u && L.r == N - 1);
+  const bool hit_a = board_any(L.valid && side_a, L.seglo, L.seghi);
+  const bool hit_b = board_any(L.valid && side_b, L.seglo, L.seghi);
+  const bool won = moved && hit_a && hit_b;
+
+  const int mover = wtm ? 1 - m.bp : m.bp;
+  m.steps += moved ? 1 : 0;
+  m.wtm = wtm ^ (moved ? 1 : 0);
+  const bool ended = illegal_now || won;
+  const float r_mover = won ? 1.f : (illegal_now ? -1.f : 0.f);
+  const float r_other = won ? -1.f : (illegal_now ? 1.f : 0.f);
+  m.illegal += illegal_now ? 1u : 0u;
+  m.term = (m.term || ended) ? 1 : 0;
+  if (ended && a.auto_reset) {   // Sec. 4.1: back to the initial state within the same ply
+    m.episode += 1u;
+    bk = 0u; wt = 0u;
+    m.steps = 0; m.wtm = 0; m.term = 0;
+    m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
+  }
+  if (L.valid && L.r == 0 && !skip) {
+    a.rew[2 * (size_t)L.b + mover] = r_mover;
+    a.rew[2 * (size_t)L.b + 1 - mover] = r_other;
+    a.term[L.b] = (ended || frozen) ? 1 : 0;
+    a.meta[L.b] = pack_meta(m);
+  }
+  const uint32_t word_new = bk | (wt << 16);
+  if (L.valid && word_new != word) a.rows[(size_t)L.b * N + L.r] = word_new;
+
+  emit_outputs(L, bk, wt, m, wave, a.B, a.mask, a.obs, lds_mask[wib], lds_obs[wib], lut);
+
+  if (SAMPLE) {
+    const bool wait = a.start_t && L.boardok && a.sample_t < (uint32_t)a.start_t[L.b];
+    const int next = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.sample_seed, a.sample_t, wait);
+    if (L.valid && L.r == 0) a.next_actions[L.b] = next;
+  }
+}
+
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uint32_t* rows, const uint4* meta, int B, uint8_t* mask, uint8_t* obs) {
+  __shared__ uint2 lut[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
+  __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const Lane L(wave, lane, B);
+  const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
+  const Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0u, 0u, 0u, 0u));
+  fill_spread_table(lut);
+  if (wave * W >= B) return;
+  emit_outputs(L, word & 0xFFFFu, word >> 16, m, wave, B, mask, obs, lds_mask[wib], lds_obs[wib], lut);
+}
+
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_random_actions_kernel(const uint32_t* rows, const uint4* meta, int B, uint32_t seed, uint32_t t,
+                                                                                const int32_t* start_t, int32_t* actions) {
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  if (wave * W >= B) return;
+  const Lane L(wave, lane, B);
+  const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
+  const Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0u, 0u, 0u, 0u));
+  const bool wait = start_t && L.boardok && t < (uint32_t)start_t[L.b];
+  const int next = draw_action(L, L.full & ~((word & 0xFFFFu) | (word >> 16)), m.steps == 1, seed, t, wait);
+  if (L.valid && L.r == 0) actions[L.b] = next;
+}
+
+// first = 1: episode 0 (init); first = 0: the next episode of every game
+__global__ void hex_reset_kernel(uint32_t* rows, uint4* meta, float* rew, uint8_t* term, int B, uint32_t seed, int first) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)B * N) return;
+  rows[i] = 0u;
+  if (i < (size_t)B) {
+    Meta m;
+    m.steps = 0; m.wtm = 0; m.term = 0;
+    m.episode = first ? 0u : meta[i].y + 1u;
+    m.illegal = first ? 0u : meta[i].z;
+    m.bp = (int)(env_hash(seed, 1u, (uint32_t)i, m.episode) & 1u);
+    meta[i] = pack_meta(m);
+    rew[2 * i] = 0.f; rew[2 * i + 1] = 0.f;
+    term[i] = 0;
+  }
+}
+
+__global__ void hex_current_player_kernel(const uint4* meta, int B, uint8_t* dst) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const Meta m = unpack_meta(meta[b]);
+  dst[b] = (uint8_t)(m.wtm ? 1 - m.bp : m.bp);
+}
+
+struct Canon {
+  int8_t* board; int8_t* to_play; int32_t* steps; uint8_t* terminated; uint8_t* black_player; uint32_t* episode; uint32_t* illegal;
+};
+
+__global__ void hex_export_kernel(const uint32_t* rows, const uint4* meta, int B, Canon c) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one thread per row
+  if (i >= (size_t)B * N) return;
+  if (c.board) {
+    const uint32_t w = rows[i];
+    for (int col = 0; col < N; ++col) c.board[i * N + col] = (int8_t)(((w >> col) & 1u) ? 1 : (((w >> (16 + col)) & 1u) ? -1 : 0));
+  }
+  if (i < (size_t)B) {
+    const Meta m = unpack_meta(meta[i]);
+    if (c.to_play) c.to_play[i] = (int8_t)(m.wtm ? -1 : 1);
+    if (c.steps) c.steps[i] = m.steps;
+    if (c.terminated) c.terminated[i] = (uint8_t)m.term;
+    if (c.black_player) c.black_player[i] = (uint8_t)m.bp;
+    if (c.episode) c.episode[i] = m.episode;
+    if (c.illegal) c.illegal[i] = m.illegal;
+  }
+}
+
+__global__ void hex_import_kernel(uint32_t* rows, uint4* meta, float* rew, uint8_t* term, int B, Canon c) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)B * N) return;
+  uint32_t w = 0u;
+  for (int col = 0; col < N; ++col) {
+    const int8_t v = c.board[i * N + col];
+    w |= (v > 0 ? 1u : 0u) << col;
+    w |= (v < 0 ? 1u : 0u) << (16 + col);
+  }
+  rows[i] = w;
+  if (i < (size_t)B) {
+    Meta m;
+    m.steps = c.steps[i] & 0xFF; m.wtm = c.to_play[i] < 0 ? 1 : 0; m.term = c.terminated[i] ? 1 : 0; m.bp = c.black_player[i] & 1;
+    m.episode = c.episode[i]; m.illegal = meta[i].z;
+    meta[i] = pack_meta(m);
+    rew[2 * i] = 0.f; rew[2 * i + 1] = 0.f;
+    term[i] = (uint8_t)m.term;
+  }
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t state_layout(int B, size_t* off_meta, size_t* off_rew, size_t* off_term) {
+  size_t o = align_up((size_t)B * N * sizeof(uint32_t), 256);
+  if (off_meta) *off_meta = o;
+  o += align_up((size_t)B * sizeof(uint4), 256);
+  if (off_rew) *off_rew = o;
+  o += align_up((size_t)B * 2 * sizeof(float), 256);
+  if (off_term) *off_term = o;
+  o += align_up((size_t)B, 256);
+  return o;
+}
+
+}  // namespace
+
+struct pgxhex_ctx {
+  int B;
+  uint32_t seed;
+  int auto_reset;
+  hipStream_t stream;
+  uint32_t* rows;
+  uint4* meta;
+  float* rew_int;
+  uint8_t* term_int;
+  uint8_t* mask_out;
+  uint8_t* obs_out;
+  float* rew_out;
+  uint8_t* term_out;
+};
+
+namespace {
+
+unsigned blocks_for(int B) {
+  const unsigned waves = (unsigned)((B + W - 1) / W);
+  return (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+}
+unsigned row_blocks(int B) { return (unsigned)(((size_t)B * N + 255) / 256); }
+
+int launch_emit(pgxhex_ctx* h, uint8_t* mask, uint8_t* obs) {
+  hipLaunchKernelGGL(hex_emit_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->rows, h->meta, h->B, mask, obs);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+int launch_reset(pgxhex_ctx* h, int first) {
+  hipLaunchKernelGGL(hex_reset_kernel, dim3(row_blocks(h->B)), dim3(256), 0, h->stream, h->rows, h->meta, h->rew_out, h->term_out, h->B, h->seed, first);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+int launch_step(pgxhex_ctx* h, const int32_t* actions, bool sample, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* next) {
+  StepArgs a;
+  a.rows = h->rows; a.meta = h->meta; a.actions = actions; a.rew = h->rew_out; a.term = h->term_out; a.mask = h->mask_out; a.obs = h->obs_out;
+  a.B = h->B; a.seed = h->seed; a.auto_reset = h->auto_reset;
+  a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
+  if (sample) hipLaunchKernelGGL(hex_step_kernel<true>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  else hipLaunchKernelGGL(hex_step_kernel<false>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t pgxhex_state_bytes(int32_t batch) { return batch > 0 ? state_layout(batch, nullptr, nullptr, nullptr) : 0; }
+
+int32_t pgxhex_boards_per_wavefront(void) { return W; }
+
+int pgxhex_init(pgxhex_t* out, int32_t batch, uint32_t seed, const pgxhex_opts* opts, void* state_dev, size_t state_bytes) {
+  if (!out) return PGXHEX_EINVAL;
+  *out = nullptr;
+  if (batch <= 0 || !state_dev || ((uintptr_t)state_dev & 255u) != 0) return PGXHEX_EINVAL;
+  size_t off_meta, off_rew, off_term;
+  if (state_bytes < state_layout(batch, &off_meta, &off_rew, &off_term)) return PGXHEX_EINVAL;
+  pgxhex_ctx* h = (pgxhex_ctx*)calloc(1, sizeof(pgxhex_ctx));
+  if (!h) return PGXHEX_ENOMEM;
+  h->B = batch; h->seed = seed;
+  h->auto_reset = (opts && opts->auto_reset) ? 1 : 0;
+  h->stream = opts ? (hipStream_t)opts->stream : nullptr;
+  uint8_t* base = (uint8_t*)state_dev;
+  h->rows = (uint32_t*)base;
+  h->meta = (uint4*)(base + off_meta);
+  h->rew_int = (float*)(base + off_rew);
+  h->term_int = base + off_term;
+  h->rew_out = h->rew_int; h->term_out = h->term_int;
+  int rc = launch_reset(h, 1);
+  if (rc == PGXHEX_OK) {
+    hipError_t e = hipStreamSynchronize(h->stream);
+    if (e != hipSuccess) { g_last_hip = (int)e; rc = PGXHEX_EHIP; }
+  }
+  if (rc != PGXHEX_OK) { free(h); return rc; }
+  *out = h;
+  return PGXHEX_OK;
+}
+
+int pgxhex_destroy(pgxhex_t h) {
+  if (!h) return PGXHEX_EINVAL;
+  free(h);
+  return PGXHEX_OK;
+}
+
+int pgxhex_reset(pgxhex_t h) {
+  if (!h) return PGXHEX_EINVAL;
+  int rc = launch_reset(h, 0);
+  if (rc != PGXHEX_OK) return rc;
+  if (h->mask_out || h->obs_out) return launch_emit(h, h->mask_out, h->obs_out);
+  return PGXHEX_OK;
+}
+
+int pgxhex_bind_outputs(pgxhex_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
+  if (!h) return PGXHEX_EINVAL;
+  float* new_rew = rewards_dev ? rewards_dev : h->rew_int;
+  uint8_t* new_term = terminated_dev ? terminated_dev : h->term_int;
+  if (new_rew != h->rew_out) HIPCHK(hipMemcpyAsync(new_rew, h->rew_out, (size_t)h->B * 2 * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+  if (new_term != h->term_out) HIPCHK(hipMemcpyAsync(new_term, h->term_out, (size_t)h->B, hipMemcpyDeviceToDevice, h->stream));
+  h->rew_out = new_rew; h->term_out = new_term;
+  h->mask_out = mask_dev; h->obs_out = obs_dev;
+  if (mask_dev || obs_dev) return launch_emit(h, mask_dev, obs_dev);
+  return PGXHEX_OK;
+}
+
+int pgxhex_step(pgxhex_t h, const int32_t* actions_dev) {
+  if (!h || !actions_dev) return PGXHEX_EINVAL;
+  return launch_step(h, actions_dev, false, 0u, 0u, nullptr, nullptr);
+}
+
+int pgxhex_step_sample(pgxhex_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* next_actions_dev) {
+  if (!h || !actions_dev || !next_actions_dev || next_actions_dev == actions_dev) return PGXHEX_EINVAL;
+  return launch_step(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev);
+}
+
+int pgxhex_random_actions(pgxhex_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev) {
+  if (!h || !actions_dev) return PGXHEX_EINVAL;
+  hipLaunchKernelGGL(hex_random_actions_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->rows, h->meta, h->B, seed, t,
+                     start_t_dev, actions_dev);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+int pgxhex_legal_mask(pgxhex_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXHEX_EINVAL;
+  return launch_emit(h, dst_dev, nullptr);
+}
+
+int pgxhex_observe(pgxhex_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXHEX_EINVAL;
+  return launch_emit(h, nullptr, dst_dev);
+}
+
+int pgxhex_rewards(pgxhex_t h, float* dst_dev) {
+  if (!h || !dst_dev) return PGXHEX_EINVAL;
+  if (dst_dev != h->rew_out) HIPCHK(hipMemcpyAsync(dst_dev, h->rew_out, (size_t)h->B * 2 * sizeof(float), hipMemcpyDeviceToDevice, h->stream));
+  return PGXHEX_OK;
+}
+
+int pgxhex_terminated(pgxhex_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXHEX_EINVAL;
+  if (dst_dev != h->term_out) HIPCHK(hipMemcpyAsync(dst_dev, h->term_out, (size_t)h->B, hipMemcpyDeviceToDevice, h->stream));
+  return PGXHEX_OK;
+}
+
+int pgxhex_current_player(pgxhex_t h, uint8_t* dst_dev) {
+  if (!h || !dst_dev) return PGXHEX_EINVAL;
+  hipLaunchKernelGGL(hex_current_player_kernel, dim3((unsigned)((h->B + 255) / 256)), dim3(256), 0, h->stream, h->meta, h->B, dst_dev);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+int pgxhex_export_state(pgxhex_t h, int8_t* board_dev, int8_t* to_play_dev, int32_t* steps_dev, uint8_t* terminated_dev, uint8_t* black_player_dev,
+                        uint32_t* episode_dev, uint32_t* illegal_dev) {
+  if (!h) return PGXHEX_EINVAL;
+  Canon c{board_dev, to_play_dev, steps_dev, terminated_dev, black_player_dev, episode_dev, illegal_dev};
+  hipLaunchKernelGGL(hex_export_kernel, dim3(row_blocks(h->B)), dim3(256), 0, h->stream, h->rows, h->meta, h->B, c);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
+}
+
+int pgxhex_import_state(pgxhex_t h, const int8_t* board_dev, const int8_t* to_play_dev, const int32_t* steps_dev, const uint8_t* terminated_dev,
+                        const uint8_t* black_player_dev, const uint32_t* episode_dev) {
+  if (!h || !board_dev || !to_play_dev || !steps_dev || !terminated_dev || !black_player_dev || !episode_dev) return PGXHEX_EINVAL;
+  Canon c{(int8_t*)board_dev, (int8_t*)to_play_dev, (int32_t*)steps_dev, (uint8_t*)terminated_dev, (uint8_t*)black_player_dev, (uint32_t*)episode_dev,
+          nullptr};
+  hipLaunchKernelGGL(hex_import_kernel, dim3(row_blocks(h->B)), dim3(256), 0, h->stream, h->rows, h->meta, h->rew_out, h->term_out, h->B, c);
+  HIPCHK(hipGetLastError());
+  if (h->mask_out || h->obs_out) return launch_emit(h, h->mask_out, h->obs_out);
+  return PGXHEX_OK;
+}
+
+int pgxhex_sync(pgxhex_t h) {
+  if (!h) return PGXHEX_EINVAL;
+  HIPCHK(hipStreamSynchronize(h->stream));
+  return PGXHEX_OK;
+}
+
+const char* pgxhex_strerror(int code) {
+  switch (code) {
+    case PGXHEX_OK: return "ok";
+    case PGXHEX_EINVAL: return "invalid argument";
+    case PGXHEX_EHIP: return "HIP runtime error";
+    case PGXHEX_ENOMEM: return "out of host memory";
+    default: return "unknown error";
+  }
+}
+
+int pgxhex_last_hip_error(void) { return g_last_hip; }
+
+}  // extern "C"

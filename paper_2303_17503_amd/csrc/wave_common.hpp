@@ -1,0 +1,93 @@
+// wave_common.hpp -- wavefront-level building blocks shared by the game kernels of this library (gfx950, wave64).
+//
+// Mapping they serve: one board row per lane, several boards per wavefront separated by all-zero sentinel
+// lanes, so that a one-lane DPP shift brings every row its north / south neighbour; board-wide facts come from
+// ballots masked with the board's lane segment; byte outputs (legal mask, observation planes; Fig. 2 and
+// Table 1 of the Pgx paper, arXiv 2303.17503) are staged as a bit stream in LDS and expanded 16 bits ->
+// 16 bytes per lane through a 256-entry LDS table.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pgxwave {
+
+// counter-based hash of (seed, tag, env, t); tag 0 = action draw, tag 1 = seat draw (t = episode)
+__device__ __forceinline__ uint32_t mixer(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du;
+  x ^= x >> 15; x *= 0x846ca68bu;
+  x ^= x >> 16;
+  return x;
+}
+__device__ __forceinline__ uint32_t env_hash(uint32_t seed, uint32_t tag, uint32_t env, uint32_t t) {
+  return mixer(mixer(mixer(seed + 0x9E3779B9u * (tag + 1u)) ^ env) ^ t);
+}
+
+// ------------------------------------------------------------------------------------------------
+// cross-lane primitives.  All of them must be called with every lane of the wavefront active.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t from_lane_below(uint32_t x) {  // lane i receives lane i-1, lane 0 receives 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x138 /* wave_shr:1 */, 0xF, 0xF, true);
+}
+__device__ __forceinline__ uint32_t from_lane_above(uint32_t x) {  // lane i receives lane i+1, lane 63 receives 0
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x130 /* wave_shl:1 */, 0xF, 0xF, true);
+}
+// A fact about a whole board, known to every lane of the board: does `pred` hold in any of its rows?
+// (seglo/seghi = the lanes holding the rows of the calling lane's board)
+__device__ __forceinline__ bool board_any(bool pred, uint32_t seglo, uint32_t seghi) {
+  const uint64_t m = __ballot(pred);
+  return (((uint32_t)m & seglo) | ((uint32_t)(m >> 32) & seghi)) != 0u;
+}
+
+// LDS traffic between the lanes of one wavefront needs no hardware barrier (a wavefront's LDS operations
+// execute in program order); this only keeps the compiler from moving accesses across the hand-over.
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ------------------------------------------------------------------------------------------------
+// bit stream -> byte stream.  `bits` (LDS) holds bit (head+i) = byte i of the destination, head = the
+// destination's offset from the previous 16-byte boundary.  Whole aligned 16-byte groups are written as
+// vectors (ROUNDS rounds of 64 lanes cover them all), the ragged ends byte by byte.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
+
+// 256-entry table in LDS: entry x = the eight bytes (0/1) of the bits of x.  Filled once per block.
+__device__ __forceinline__ void fill_spread_table(uint2* lut) {
+  for (uint32_t x = threadIdx.x; x < 256u; x += blockDim.x) lut[x] = make_uint2(spread4(x & 15u), spread4(x >> 4));
+  __syncthreads();
+}
+
+template <int ROUNDS>
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
+  const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
+  uint8_t* base = dst - head;
+  const uint32_t total = head + nbytes;
+  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1, at most 64*ROUNDS of them
+  const uint32_t mine = m0 + (uint32_t)lane;             // this lane's group in round 0; round i adds 64*i
+  const uint16_t* src = (const uint16_t*)bits + mine;
+  uint4* out = (uint4*)base + mine;
+  constexpr int GROUP = 6;   // rounds in flight at a time (bounds the registers held by pending LDS reads)
+#pragma unroll
+  for (int g = 0; g < ROUNDS; g += GROUP) {
+    uint32_t v[GROUP];
+#pragma unroll
+    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = (mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+#pragma unroll
+    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
+      const uint2 lo = lut[v[i - g] & 255u], hi = lut[v[i - g] >> 8];
+      if (mine + 64u * i < m1) out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (lane < 32) {
+    uint32_t i = lane & 15u, pos;
+    bool ok;
+    if (lane < 16) { pos = i; ok = head != 0u && i >= head; }
+    else { pos = (m1 << 4) + i; ok = i < (total & 15u); }
+    if (ok) base[pos] = (uint8_t)((bits[pos >> 5] >> (pos & 31u)) & 1u);
+  }
+}
+
+}  // namespace pgxwave

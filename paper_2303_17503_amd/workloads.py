@@ -23,6 +23,7 @@ class Config:
     warmup_max: int = 0   # config 4: each environment first plays k ~ U[0, warmup_max] plies
     emit_obs: bool = True
     komi_x2: int = 15
+    game: str = "go"
 
 
 CONFIGS = [
@@ -31,6 +32,13 @@ CONFIGS = [
     Config("go19_b1024_fullgame", 19, 1024, 2, False, 722),
     Config("go19_b16384_autoreset_obs", 19, 16384, 3, True, 2000),
     Config("go19_b65536_midgame", 19, 65536, 4, True, 500, warmup_max=300),
+]
+
+# Hex 11x11 (the second workload): random legal play from the empty board as in Sec. 4.1; a game lasts at most 122 plies
+HEX_CONFIGS = [
+    Config("hex11_b1024_fullgame", 11, 1024, 5, False, 122, game="hex"),
+    Config("hex11_b16384_autoreset", 11, 16384, 6, True, 1000, game="hex"),
+    Config("hex11_b262144_autoreset", 11, 262144, 7, True, 500, game="hex"),
 ]
 
 _M = np.uint64(0xFFFFFFFF)

@@ -12,10 +12,10 @@ from paper_2303_17503_amd import workloads
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "pgxgo.h")).read()
+def declared_functions(header="pgxgo.h", prefix="pgxgo_"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(pgxgo_[a-z_0-9]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"[a-z_0-9]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -24,6 +24,33 @@ def test_library_exports_every_declared_symbol():
     L = C.CDLL(pg.LIB_PATH)
     for n in names:
         assert hasattr(L, n), n
+
+
+def test_library_exports_every_declared_hex_symbol():
+    names = declared_functions("pgxhex.h", "pgxhex_")
+    assert len(names) >= 18 and "pgxhex_step" in names and "pgxhex_init" in names and "pgxhex_step_sample" in names
+    L = C.CDLL(pg.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_hex_argument_errors_need_no_gpu():
+    from paper_2303_17503_amd import hex_binding
+    L = hex_binding.lib()
+    h = C.c_void_p()
+    assert L.pgxhex_boards_per_wavefront() == 5
+    assert L.pgxhex_state_bytes(0) == 0 and L.pgxhex_state_bytes(-3) == 0
+    b1, b2 = L.pgxhex_state_bytes(1000), L.pgxhex_state_bytes(2000)
+    assert 1000 * (11 * 4 + 16 + 8 + 1) <= b1 < b2 < 2 * b1 + 4096
+    assert L.pgxhex_init(C.byref(h), 4, 0, None, None, 0) == -1                      # null state buffer
+    assert L.pgxhex_init(C.byref(h), 0, 0, None, C.c_void_p(256), 1 << 20) == -1     # batch
+    assert L.pgxhex_init(C.byref(h), 4, 0, None, C.c_void_p(256), 16) == -1          # buffer too small
+    assert L.pgxhex_init(C.byref(h), 4, 0, None, C.c_void_p(260), 1 << 20) == -1     # misaligned
+    assert L.pgxhex_init(None, 4, 0, None, C.c_void_p(256), 1 << 20) == -1
+    assert L.pgxhex_step(None, None) == -1 and L.pgxhex_destroy(None) == -1 and L.pgxhex_step_sample(None, None, 0, 0, None, None) == -1
+    assert L.pgxhex_strerror(-1) == b"invalid argument" and L.pgxhex_strerror(0) == b"ok"
+    header = open(os.path.join(ROOT, "include", "pgxhex.h")).read()
+    assert "#define PGXHEX_ACTIONS 122" in header and "#define PGXHEX_OBS_BYTES 484" in header   # Table 1
 
 
 def test_size_queries_match_the_paper_tables():
