@@ -47,6 +47,33 @@ def read_traffic(path):
         return None
 
 
+def hex_bytes_per_ply(with_obs):
+    """The same accounting for Hex 11x11: action, packed position in/out, scalars, 122 mask bytes, 484 observation
+    bytes, rewards + terminated.  707 B with the observation."""
+    return algorithmic_bytes_per_ply_generic(11, 4 if with_obs else 0, history_reads=1)
+
+
+def algorithmic_bytes_per_ply_generic(N, planes, history_reads):
+    P = N * N
+    packed = (P + 7) // 8
+    return 4 + history_reads * 2 * packed + 24 + 2 * packed + (P + 1) + P * planes + 9
+
+
+def device_copy_gbs(nbytes):
+    """A plain device copy of as many bytes as one step writes: a practical ceiling, and the kernel of known size that
+    calibrates the HBM counters."""
+    import torch
+
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(5): dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(50): dst.copy_(src)
+    e1.record(); torch.cuda.synchronize()
+    return 2 * nbytes * 50 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def cpu_baseline(cfg, steps, n_threads, envs_per_thread):
     """The CPU oracle as it stands on the same workload: the first n_threads*envs_per_thread environments
     of the configuration, all `steps` plies, sharded over host threads (the C calls release the GIL)."""
@@ -55,11 +82,18 @@ def cpu_baseline(cfg, steps, n_threads, envs_per_thread):
     import oracle
 
     oracle.lib()
+    if cfg.game == "hex":
+        from oracle import hex as hx
+        hx.lib()
     done = [0] * n_threads
 
     def work(i):
         ids = np.arange(i * envs_per_thread, (i + 1) * envs_per_thread, dtype=np.int32)
-        o = oracle.GoOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids)
+        if cfg.game == "hex":
+            from oracle import hex as hx
+            o = hx.HexOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, auto_reset=cfg.auto_reset, env_ids=ids)
+        else:
+            o = oracle.GoOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids)
         for t in range(steps):
             o.step(o.random_actions(cfg.seed, t))
         done[i] = envs_per_thread * steps
@@ -81,7 +115,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--config", type=int, default=3, help="index into workloads.CONFIGS (3 = headline)")
+    ap.add_argument("--game", choices=["go", "hex"], default="go", help="go: the headline workload; hex: the second workload (Hex 11x11)")
+    ap.add_argument("--config", type=int, default=None, help="index into workloads.CONFIGS (default 3 = headline) or, with --game hex, "
+                                                             "into workloads.HEX_CONFIGS (default 2)")
     ap.add_argument("--mode", choices=["fused", "separate", "rollout"], default="fused",
                     help="fused: one launch per ply, the step kernel also draws the next action (headline); separate: sampler kernel + "
                          "step kernel per ply; rollout: --rollout-len plies per launch with the state kept in registers")
@@ -101,7 +137,9 @@ def main():
     from paper_2303_17503_amd import workloads
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    cfg = workloads.CONFIGS[args.config]
+    if args.game == "hex":
+        return bench_hex(args, workloads.HEX_CONFIGS[2 if args.config is None else args.config])
+    cfg = workloads.CONFIGS[3 if args.config is None else args.config]
     B, N, seed = cfg.batch, cfg.board_size, cfg.seed
     K, Wm = args.steps, args.warmup
     with_obs = not args.no_obs
@@ -173,16 +211,7 @@ def main():
             kern_ms = sum(a.elapsed_time(b) for a, b in events) / n_ev
         kname = "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
 
-    # a plain device copy of the same number of bytes as one step writes, as a practical ceiling
-    nbytes = B * (N * N * 17 + N * N + 1)
-    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
-    dst = torch.empty_like(src)
-    for _ in range(5): dst.copy_(src)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(50): dst.copy_(src)
-    e1.record(); torch.cuda.synchronize()
-    copy_gbs = 2 * nbytes * 50 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    copy_gbs = device_copy_gbs(B * (N * N * 17 + N * N + 1))
 
     bytes_ply = algorithmic_bytes_per_ply(N, with_obs)
     achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
@@ -216,6 +245,59 @@ def main():
                                "sample": f"first {n_threads * envs_per_thread} environments of {cfg.name} (same seed and sampler), "
                                          f"{cpu_steps} plies each, {envs_per_thread} per host thread; warm-up of config 4 not replayed",
                                "single_core_value": single}
+    print(json.dumps(out))
+
+
+def bench_hex(args, cfg):
+    """The same protocol for Hex 11x11: one launch per ply (step + next random action), mask and observation every ply."""
+    import torch
+
+    import paper_2303_17503_amd as pg
+
+    assert args.mode == "fused", "--game hex has the fused mode only"
+    B, seed, K, Wm = cfg.batch, cfg.seed, args.steps, args.warmup
+    with_obs = not args.no_obs
+    env = pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
+    mask = env.new_mask()
+    obs = env.new_obs() if with_obs else None
+    rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
+    term = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    env.bind_outputs(mask, obs, rew, term)
+    acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
+    env.random_actions(seed, 0, out=acts[0])
+    for t in range(Wm):
+        env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for t in range(Wm, Wm + K):
+        env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = ev0.elapsed_time(ev1) / K
+    copy_gbs = device_copy_gbs(B * (484 + 122))
+    bytes_ply = hex_bytes_per_ply(with_obs)
+    achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"hex_step_kernel_{cfg.name}_pmc.txt")) if with_obs else None
+    out = {
+        "metric": "Hex env steps/sec on 1 MI355X (11x11, random legal play); HBM GB/s % peak",
+        "value": B * K / wall, "unit": "env steps/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": wall / K * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": cfg.name, "board_size": 11, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset, "observation": with_obs,
+                   "mode": "fused"},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "kernel": "hex_step_kernel<true>", "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
+                     "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
+    }
+    if not args.no_cpu_baseline:
+        n_threads = max(1, min(16, os.cpu_count() or 1))
+        cpu_steps = min(K, 2000)
+        single, multi = cpu_baseline(cfg, cpu_steps, n_threads, 64)
+        out["cpu_baseline"] = {"value": multi, "unit": "env steps/s", "cores": n_threads, "kind": "oracle",
+                               "sample": f"first {n_threads * 64} environments of {cfg.name} (same seed and sampler), {cpu_steps} plies each, "
+                                         "64 per host thread", "single_core_value": single}
     print(json.dumps(out))
 
 

@@ -50,6 +50,7 @@ constexpr int MASK_ROUNDS = (W * A / 16 + 63) / 64;
 static_assert(A == PGXHEX_ACTIONS && OBS == PGXHEX_OBS_BYTES, "header constants");
 static_assert((15 + W * A + 31) / 32 <= MASK_DW, "mask stream fits its staging area");
 static_assert(N <= 16, "a row holds both colours in one dword");
+static_assert(N == 11, "the action decode divides by 11 with a multiply and a shift");
 
 // per-board scalars, one 16-byte record: x = steps[0:8) | white_to_move[8] | terminated[9] | black_player[10],
 // y = episode, z = illegal actions received
@@ -216,8 +217,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   const bool live = !skip && !frozen;
   const uint32_t E = L.full & ~(bk | wt);
   const bool want_point = live && act >= 0 && act < P;
-  const int pr = want_point ? act / N : -100;
-  const int pc = want_point ? act - pr * N : 0;
+  const int row_of = (int)(__umul24((uint32_t)act & 127u, 745u) >> 13);   // act / 11 for 0 <= act < 128
+  const int pr = want_point ? row_of : -100;
+  const int pc = want_point ? act - row_of * N : 0;
   const uint32_t pbit = (L.valid && L.r == pr) ? (1u << pc) : 0u;
   const bool point_ok = want_point && board_any((E & pbit) != 0u, L.seglo, L.seghi);
   const bool swap_ok = live && act == P && m.steps == 1;
@@ -226,12 +228,15 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   const int wtm = m.wtm;
 
   // swap rule: on the second turn the board holds Black's lone stone (r0,c0); it comes off and a white stone goes to (c0,r0)
-  const uint64_t nz = __ballot(bk != 0u);
-  const uint32_t zlo = (uint32_t)nz & L.seglo, zhi = (uint32_t)(nz >> 32) & L.seghi;
-  const int src = zlo ? __ffs(zlo) - 1 : (zhi ? 31 + __ffs(zhi) : 0);
-  const int r0 = src - (L.j * STRIDE + 1);
-  const int c0 = __ffs(__shfl((int)bk, src)) - 1;
-  const uint32_t swapped = (L.valid && L.r == c0 && r0 >= 0) ? (1u << (r0 & 15)) : 0u;
+  uint32_t swapped = 0u;
+  if (__ballot(swap_ok) != 0ull) {   // once per game at most: keep it off the common path
+    const uint64_t nz = __ballot(bk != 0u);
+    const uint32_t zlo = (uint32_t)nz & L.seglo, zhi = (uint32_t)(nz >> 32) & L.seghi;
+    const int src = zlo ? __ffs(zlo) - 1 : (zhi ? 31 + __ffs(zhi) : 0);
+    const int r0 = src - (L.j * STRIDE + 1);
+    const int c0 = __ffs(__shfl((int)bk, src)) - 1;
+    swapped = (L.valid && L.r == c0 && r0 >= 0) ? (1u << (r0 & 15)) : 0u;
+  }
   const uint32_t placed = swap_ok ? swapped : (point_ok ? pbit : 0u);
   if (swap_ok) { bk = 0u; wt = swapped; }
   else if (wtm) wt |= placed;
