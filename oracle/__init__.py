@@ -36,6 +36,7 @@ def lib():
         L.oracle_legal_chains.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.oracle_area.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.oracle_chain.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.oracle_set_superko.argtypes = [C.c_void_p, C.c_int]
         _lib = L
     return _lib
 
@@ -72,7 +73,7 @@ class GoOracle:
     """Batched Go environment on the CPU (paper Fig. 2 API: init / step / observation /
     legal_action_mask / rewards / terminated / current_player)."""
 
-    def __init__(self, batch, board_size, seed=0, komi_x2=15, max_steps=0, auto_reset=False, env_ids=None):
+    def __init__(self, batch, board_size, seed=0, komi_x2=15, max_steps=0, auto_reset=False, env_ids=None, superko=False):
         self.B, self.N = int(batch), int(board_size)
         self.P = self.N * self.N
         self.A = self.P + 1
@@ -80,6 +81,12 @@ class GoOracle:
         self._h = lib().oracle_create(self.B, self.N, seed & 0xFFFFFFFF, komi_x2, max_steps, int(auto_reset), _p(ids))
         if not self._h:
             raise ValueError("oracle_create rejected its arguments")
+        if superko:
+            self.set_superko(True)
+
+    def set_superko(self, on):
+        """Positional superko: a play that recreates an earlier position of the game is an illegal action."""
+        lib().oracle_set_superko(self._h, int(bool(on)))
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

@@ -25,6 +25,7 @@
 // Unpinned: agreement with the upstream Pgx library's own choices where the
 // paper is silent (no upstream code or traces are available here).
 
+#include <array>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -47,12 +48,16 @@ struct Env {
   int black_player;           // player id (0/1) holding black this episode (Fig. 2: current_player independent of colour)
   uint32_t episode;           // number of resets so far
   uint32_t env_id;            // global environment index used by the hashes
+  // positional superko (option): every whole-board position this episode has shown so far, the empty
+  // starting board included, kept literally
+  std::vector<std::array<int8_t, kMaxP>> seen;
 };
 
 struct Oracle {
   int B, N, P;
   uint32_t seed;
   int komi_x2, max_steps, auto_reset;
+  int superko = 0;                // 1: a play that recreates an earlier position of the game is an illegal action
   std::vector<Env> env;
   std::vector<float> out_rew;     // [B][2], by player id: values of the last step call
   std::vector<uint8_t> out_term;  // [B]
@@ -200,12 +205,35 @@ void area_score(const int8_t* board, int N, int* area_black, int* area_white) {
   *area_black = ab; *area_white = aw;
 }
 
+// ---- positional superko (Appendix C "Go": Tromp-Taylor rules; their repetition rule forbids a play that
+// recreates any earlier whole-board position of the game).  Reading: enforced when the move is played (the
+// offender loses like for any illegal action); the legal mask keeps showing the simple-ko set.
+void remember(Env& e) {
+  std::array<int8_t, kMaxP> pos;
+  std::memcpy(pos.data(), e.board, kMaxP);
+  e.seen.push_back(pos);
+}
+bool seen_before(const Env& e, const int8_t* board) {
+  for (const auto& pos : e.seen)
+    if (std::memcmp(pos.data(), board, kMaxP) == 0) return true;
+  return false;
+}
+// would playing `col` on p (a move the simple rules allow) recreate an earlier position?
+bool repeats_position(const Env& e, int N, int p, int col) {
+  int8_t tmp[kMaxP];
+  std::memcpy(tmp, e.board, kMaxP);
+  place_and_capture(tmp, N, p, col, nullptr);
+  return seen_before(e, tmp);
+}
+
 void env_reset(Oracle* o, Env& e) {
   std::memset(e.board, 0, sizeof e.board);
   std::memset(e.hist, 0, sizeof e.hist);
   e.to_play = 1; e.ko = -1; e.steps = 0; e.passes = 0; e.terminated = 0;
   // Fig. 2: which player acts first is drawn by a PRNG, independently of colour.
   e.black_player = (int)(hash4(o->seed, 1u, e.env_id, e.episode) & 1u);
+  e.seen.clear();
+  if (o->superko) remember(e);
 }
 
 void env_outputs(Oracle* o, int b) {
@@ -241,7 +269,7 @@ void env_step(Oracle* o, int b, int a) {
   const int mover = (col == 1) ? e.black_player : 1 - e.black_player;
   const uint8_t* m = &o->mask[(size_t)b * (P + 1)];
   bool ended = false;
-  if (a < 0 || a > P || !m[a]) {
+  if (a < 0 || a > P || !m[a] || (o->superko && a < P && repeats_position(e, N, a, col))) {
     // Illegal action: the game ends at once, the offender loses; the position,
     // ply counter and side to move stay as they were.
     o->illegal[b] += 1;
@@ -263,6 +291,7 @@ void env_step(Oracle* o, int b, int a) {
       int n = chain_at(e.board, N, a, cells, &libs, &one);
       e.ko = (captured == 1 && lone && n == 1 && libs == 1 && one == cap_at) ? cap_at : -1;
       e.passes = 0;
+      if (o->superko) remember(e);
     }
     e.steps += 1;
     for (int i = kHist - 1; i > 0; --i) std::memcpy(e.hist[i], e.hist[i - 1], P);
@@ -288,6 +317,18 @@ void env_step(Oracle* o, int b, int a) {
     o->out_term[b] = 0;
   }
   env_outputs(o, b);
+}
+
+void rebuild_seen(Oracle* o, Env& e) {
+  e.seen.clear();
+  if (!o->superko) return;
+  for (int i = kHist - 1; i >= 0; --i) {
+    std::array<int8_t, kMaxP> pos;
+    pos.fill(0);
+    std::memcpy(pos.data(), e.hist[i], o->P);
+    e.seen.push_back(pos);
+  }
+  remember(e);
 }
 
 }  // namespace
@@ -399,8 +440,17 @@ void oracle_import_state(void* h, const int8_t* board, const int8_t* history, co
     e.ko = ko[b]; e.to_play = to_play[b]; e.steps = steps[b]; e.passes = passes[b];
     e.terminated = terminated[b]; e.black_player = black_player[b]; e.episode = episode[b];
     o->out_rew[2 * b] = o->out_rew[2 * b + 1] = 0.f; o->out_term[b] = (uint8_t)e.terminated;
+    rebuild_seen(o, e);
     env_outputs(o, b);
   }
+}
+
+// Switches positional superko on or off.  The positions known from then on are the ones the state still
+// carries: the 8 history positions (entries from before the game started are the empty board) and the current one.
+void oracle_set_superko(void* h, int on) {
+  Oracle* o = (Oracle*)h;
+  o->superko = on ? 1 : 0;
+  for (int b = 0; b < o->B; ++b) rebuild_seen(o, o->env[b]);
 }
 
 // ---- stand-alone rule functions on a caller-supplied board (used by the pins) ----

@@ -77,7 +77,7 @@ def area(stones, N):
 class RefGame:
     """One game with the same observable behaviour as one oracle environment."""
 
-    def __init__(self, N, komi_x2=15, max_steps=None, black_player=0):
+    def __init__(self, N, komi_x2=15, max_steps=None, black_player=0, superko=False):
         self.N, self.P = N, N * N
         self.komi_x2 = komi_x2
         self.max_steps = max_steps or 2 * N * N
@@ -90,6 +90,8 @@ class RefGame:
         self.black_player = black_player
         self.rewards = [0.0, 0.0]
         self.past = []  # positions after each ply, newest last
+        self.superko = superko                 # positional superko, enforced when the move is played
+        self.shown = {frozenset()}             # every position the game has shown, as a set of (cell, colour) pairs
 
     def legal(self, a):
         if a == self.P:
@@ -98,6 +100,13 @@ class RefGame:
         if rc == self.ko:
             return False
         return try_play(self.stones, self.N, rc, self.to_play) is not None
+
+    def recreates(self, a):
+        """With superko on: would this (otherwise legal) play bring back a position the game has already shown?"""
+        if not self.superko or a == self.P:
+            return False
+        res = try_play(self.stones, self.N, divmod(a, self.N), self.to_play)
+        return res is not None and frozenset(res[0].items()) in self.shown
 
     def mask(self):
         return [1 if self.legal(a) else 0 for a in range(self.P + 1)]
@@ -110,7 +119,7 @@ class RefGame:
         self.rewards = [0.0, 0.0]
         col = self.to_play
         mover = self.black_player if col == BLACK else 1 - self.black_player
-        if not (0 <= a <= self.P) or not self.legal(a):
+        if not (0 <= a <= self.P) or not self.legal(a) or self.recreates(a):
             self.rewards[mover], self.rewards[1 - mover] = -1.0, 1.0
             self.terminated = True
             return
@@ -125,6 +134,7 @@ class RefGame:
             self.ko = next(iter(captured)) if (len(captured) == 1 and alone and len(cells) == 1 and libs == captured) else None
             self.passes = 0
         self.steps += 1
+        self.shown.add(frozenset(self.stones.items()))
         self.past.append(dict(self.stones))
         self.to_play = -col
         if self.passes == 2 or self.steps >= self.max_steps:
