@@ -74,7 +74,7 @@ def device_copy_gbs(nbytes):
     return 2 * nbytes * 50 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
 
-def cpu_baseline(cfg, steps, n_threads, envs_per_thread):
+def cpu_baseline(cfg, steps, n_threads, envs_per_thread, superko=False):
     """The CPU oracle as it stands on the same workload: the first n_threads*envs_per_thread environments
     of the configuration, all `steps` plies, sharded over host threads (the C calls release the GIL)."""
     import numpy as np
@@ -93,7 +93,8 @@ def cpu_baseline(cfg, steps, n_threads, envs_per_thread):
             from oracle import hex as hx
             o = hx.HexOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, auto_reset=cfg.auto_reset, env_ids=ids)
         else:
-            o = oracle.GoOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids)
+            o = oracle.GoOracle(envs_per_thread, cfg.board_size, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids,
+                            superko=superko)
         for t in range(steps):
             o.step(o.random_actions(cfg.seed, t))
         done[i] = envs_per_thread * steps
@@ -123,6 +124,7 @@ def main():
                          "step kernel per ply; rollout: --rollout-len plies per launch with the state kept in registers")
     ap.add_argument("--rollout-len", type=int, default=50, help="plies per launch in rollout mode")
     ap.add_argument("--rollout-slices", type=int, default=1, help="trajectory slices the rollout writes to (1 = overwrite one set of buffers)")
+    ap.add_argument("--superko", action="store_true", help="Go only: switch the positional-superko rule on (not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-obs", action="store_true", help="do not emit the observation (not the headline metric)")
     args = ap.parse_args()
@@ -145,6 +147,9 @@ def main():
     with_obs = not args.no_obs
 
     env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
+    if args.superko:
+        assert args.mode != "rollout", "the rollout kernel does not carry the superko tables"
+        env.enable_superko()
     start = workloads.start_times(cfg)
     start_dev = None if start is None else torch.as_tensor(start, device="cuda")
     pre = cfg.warmup_max          # config 4: the plies that build the mid-game positions are not part of the measurement
@@ -209,13 +214,13 @@ def main():
             run_steps(pre + Wm + K, n_ev, events)
             torch.cuda.synchronize()
             kern_ms = sum(a.elapsed_time(b) for a, b in events) / n_ev
-        kname = "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
+        kname = "go_step_superko_kernel<%d>" % N if args.superko else "go_step_kernel<%d,%s>" % (N, "true" if args.mode == "fused" else "false")
 
     copy_gbs = device_copy_gbs(B * (N * N * 17 + N * N + 1))
 
     bytes_ply = algorithmic_bytes_per_ply(N, with_obs)
     achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"go_step_kernel_{cfg.name}_pmc.txt")) if with_obs and args.mode == "fused" else None
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"go_step_kernel_{cfg.name}_pmc.txt")) if with_obs and args.mode == "fused" and not args.superko else None
     out = {
         "metric": "Go env steps/sec on 1 MI355X (19x19, batch 16384, random legal play); HBM GB/s % peak",
         "value": B * K / wall,
@@ -230,7 +235,7 @@ def main():
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "board_size": N, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset,
-                   "observation": with_obs, "mode": args.mode, "komi": cfg.komi_x2 / 2, "pre_warmup_plies_max": cfg.warmup_max,
+                   "observation": with_obs, "mode": args.mode, "superko": bool(args.superko), "komi": cfg.komi_x2 / 2, "pre_warmup_plies_max": cfg.warmup_max,
                    **({"rollout_len": args.rollout_len, "rollout_slices": args.rollout_slices} if args.mode == "rollout" else {})},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
@@ -240,7 +245,7 @@ def main():
         n_threads = max(1, min(16, os.cpu_count() or 1))
         envs_per_thread = 16
         cpu_steps = min(K, 2000)
-        single, multi = cpu_baseline(cfg, cpu_steps, n_threads, envs_per_thread)
+        single, multi = cpu_baseline(cfg, cpu_steps, n_threads, envs_per_thread, superko=args.superko)
         out["cpu_baseline"] = {"value": multi, "unit": "env steps/s", "cores": n_threads, "kind": "oracle",
                                "sample": f"first {n_threads * envs_per_thread} environments of {cfg.name} (same seed and sampler), "
                                          f"{cpu_steps} plies each, {envs_per_thread} per host thread; warm-up of config 4 not replayed",

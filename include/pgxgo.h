@@ -152,6 +152,19 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
                        const int8_t* to_play_dev, const int32_t* steps_dev, const int8_t* passes_dev,
                        const uint8_t* terminated_dev, const uint8_t* black_player_dev, const uint32_t* episode_dev);
 
+/* Positional superko (Appendix C "Go": Tromp-Taylor rules, whose repetition rule forbids a play that recreates an
+ * earlier whole-board position of the game).  Off by default (simple ko only).  Reading: the rule is enforced when
+ * the move is played -- a play that brings back a position the game has already shown is an illegal action (the
+ * game ends, offender -1 / opponent +1, position unchanged) -- while the legal mask keeps showing the simple-ko set.
+ * Positions are compared through 64-bit Zobrist keys kept in a per-game table inside table_dev.
+ *   pgxgo_superko_bytes: bytes of device memory the tables need (0 for invalid arguments); 256-byte aligned.
+ *   pgxgo_enable_superko: switches the rule on with a caller-owned buffer that must outlive the handle (or off with
+ *     table_dev = NULL).  The positions known from then on are the ones the state still carries (the 8 history
+ *     positions and the current one); the same holds after pgxgo_import_state.  Needs max_steps <= 2*N*N.
+ *     While the rule is on, pgxgo_rollout, pgxgo_step_slots and pgxgo_copy_slots return PGXGO_EINVAL. */
+size_t pgxgo_superko_bytes(int32_t batch, int32_t board_size);
+int pgxgo_enable_superko(pgxgo_t h, void* table_dev, size_t table_bytes);
+
 /* Blocks the host until everything enqueued on the handle's stream has finished. */
 int pgxgo_sync(pgxgo_t h);
 

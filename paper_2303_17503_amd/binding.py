@@ -45,6 +45,9 @@ def lib():
         L.pgxgo_export_state.argtypes = [vp] * 11
         L.pgxgo_import_state.argtypes = [vp] * 10
         L.pgxgo_sync.argtypes = [vp]
+        L.pgxgo_superko_bytes.restype = C.c_size_t
+        L.pgxgo_superko_bytes.argtypes = [i32, i32]
+        L.pgxgo_enable_superko.argtypes = [vp, vp, C.c_size_t]
         for n in ("boards_per_wavefront", "num_actions", "obs_bytes"):
             getattr(L, "pgxgo_" + n).argtypes = [i32]
             getattr(L, "pgxgo_" + n).restype = i32
@@ -205,6 +208,16 @@ class GoEnv:
 
     def sync(self):
         _check(lib().pgxgo_sync(self._h), "pgxgo_sync")
+
+    def enable_superko(self, on=True):
+        """Positional superko: a play that recreates an earlier position of the game becomes an illegal action."""
+        if not on:
+            _check(lib().pgxgo_enable_superko(self._h, None, 0), "pgxgo_enable_superko")
+            self._superko = None
+            return
+        nbytes = lib().pgxgo_superko_bytes(self.B, self.N)
+        self._superko = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        _check(lib().pgxgo_enable_superko(self._h, _ptr(self._superko), nbytes), "pgxgo_enable_superko")
 
     # ---- canonical state ------------------------------------------------------------------------------------
     STATE_FIELDS = (("board", torch.int8), ("history", torch.int8), ("ko", torch.int32), ("to_play", torch.int8),

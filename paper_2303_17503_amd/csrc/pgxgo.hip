@@ -441,6 +441,17 @@ __device__ __forceinline__ void push_history(uint32_t (&h)[Geo<N>::HD], uint32_t
   }
 }
 
+// a8: back to the initial state of the next episode (Sec. 4.1); the seat is drawn anew
+template <int N>
+__device__ __forceinline__ void reset_board(const Lane<N>& L, Row<N>& R, Meta& m, uint32_t seed) {
+#pragma unroll
+  for (int jd = 0; jd < Geo<N>::HD; ++jd) R.h[jd] = 0u;
+  R.bk = R.wt = R.ab = R.aw = 0u;
+  m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
+  m.episode += 1;
+  m.bp = (int)(env_hash(seed, 1u, (uint32_t)L.slot, m.episode) & 1u);
+}
+
 // a3-a8 for every board of the wavefront; registers in, registers out.
 // Out: rewards by player id, `flag` = the terminated output (game ended in this ply, or had ended before),
 // `captured` = the stones this ply removed, `reset` = the board was re-initialised by auto-reset.
@@ -578,14 +589,7 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
   if (ended) {
     m.term = 1;
     // ---- a8: auto-reset (Sec. 4.1) -------------------------------------------------------------------------
-    if (cfg.auto_reset) {
-#pragma unroll
-      for (int jd = 0; jd < G::HD; ++jd) R.h[jd] = 0u;
-      R.bk = R.wt = R.ab = R.aw = 0u;
-      m.ko = -1; m.steps = 0; m.passes = 0; m.wtm = 0; m.term = 0;
-      m.episode += 1;
-      m.bp = (int)(env_hash(cfg.seed, 1u, (uint32_t)L.slot, m.episode) & 1u);
-    }
+    if (cfg.auto_reset) reset_board<N>(L, R, m, cfg.seed);
   }
   flag = ended || frozen;
 }
@@ -675,6 +679,217 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
     const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// positional superko (Appendix C "Go": Tromp-Taylor rules, whose repetition rule forbids a play that recreates
+// an earlier whole-board position of the game).  Reading: enforced when the move is played -- the offender
+// loses like for any illegal action -- while the legal mask keeps showing the simple-ko set.
+// Every position is summarised by a 64-bit Zobrist key (XOR of one key per stone), updated incrementally from
+// the stones that changed; the keys of the positions a game has shown are kept in a per-game open-addressing
+// table in device memory (SLOTS entries of 8 bytes, linear probing, at most 2*N*N + 9 of them in use).
+// ------------------------------------------------------------------------------------------------
+template <int N>
+struct Zt {
+  static constexpr uint32_t SLOTS = N == 19 ? 2048u : 512u;
+  static_assert(SLOTS >= 2u * (2u * N * N + 9u), "the table stays at most half full");
+};
+
+__device__ __forceinline__ uint2 zkey(uint32_t point, uint32_t colour) {   // colour 0 black / 1 white
+  const uint32_t lo = mixer(0x9E3779B9u * (2u * point + colour + 1u));
+  return make_uint2(lo, mixer(lo + 0x85EBCA6Bu));
+}
+// the stored form of a position key: never (0,0), which marks an empty slot
+__device__ __forceinline__ uint2 zstored(uint2 k) { return make_uint2(k.x, k.y | 0x80000000u); }
+
+// XOR of the keys of the stones (black bits, white bits) of row r
+template <int N>
+__device__ __forceinline__ uint2 row_keys(int r, uint32_t black, uint32_t white) {
+  uint2 acc = make_uint2(0u, 0u);
+  for (uint32_t d = black; d; d &= d - 1u) { const uint2 k = zkey((uint32_t)(r * N + __ffs(d) - 1), 0u); acc.x ^= k.x; acc.y ^= k.y; }
+  for (uint32_t d = white; d; d &= d - 1u) { const uint2 k = zkey((uint32_t)(r * N + __ffs(d) - 1), 1u); acc.x ^= k.x; acc.y ^= k.y; }
+  return acc;
+}
+
+// every lane of a board receives the XOR of v over the board's rows; scratch = 2*W dwords of the wavefront's LDS
+template <int N>
+__device__ __forceinline__ uint2 board_xor(const Lane<N>& L, uint2 v, uint32_t* scratch) {
+  using G = Geo<N>;
+  if (L.lane < 2 * G::W) scratch[L.lane] = 0u;
+  wave_lds_fence();
+  if (L.valid && (v.x | v.y) != 0u) { atomicXor(&scratch[2 * L.j], v.x); atomicXor(&scratch[2 * L.j + 1], v.y); }
+  wave_lds_fence();
+  uint2 out = make_uint2(0u, 0u);
+  if (L.j < G::W) out = make_uint2(scratch[2 * L.j], scratch[2 * L.j + 1]);
+  wave_lds_fence();
+  return out;
+}
+
+// Looks `key` up in the board's table (tab = this board's SLOTS entries), N consecutive slots per round, one per
+// row lane.  found: the key is in the table.  Otherwise free_slot = the first empty slot from the key's home
+// slot on, where an insert goes (ok = such a slot exists; always, since the table is never more than half full).
+// pre_e / pre_base: entries a caller has already loaded for the round that starts at slot pre_base (a guess of the
+// home slot made before the key was known); pre_base = ~0u when there are none.
+template <int N>
+__device__ __forceinline__ void table_probe(const Lane<N>& L, const uint2* tab, uint2 key, bool active, uint32_t pre_base, uint2 pre_e, bool& found,
+                                            bool& ok, uint32_t& free_slot) {
+  using G = Geo<N>;
+  constexpr uint32_t MASK = Zt<N>::SLOTS - 1u;
+  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
+  found = false; ok = false; free_slot = 0u;
+  bool done = !active;
+  uint32_t base = key.x & MASK;
+  for (uint32_t round = 0; round < Zt<N>::SLOTS / N + 1u; ++round) {
+    if (__ballot(!done) == 0ull) break;
+    const bool look = L.valid && !done;
+    uint2 e = make_uint2(1u, 1u);
+    if (look) {
+      if (round == 0u && base == pre_base) e = pre_e;
+      else e = tab[(base + (uint32_t)L.r) & MASK];
+    }
+    const uint64_t em = __ballot(look && (e.x | e.y) == 0u) & seg;
+    const uint64_t mm = __ballot(look && e.x == key.x && e.y == key.y) & seg;
+    const int fe = em ? __ffsll((long long)em) - 1 : 64, fm = mm ? __ffsll((long long)mm) - 1 : 64;
+    if (!done) {
+      if (fm < fe) { found = true; done = true; }
+      else if (fe < 64) { free_slot = (base + (uint32_t)(fe - (L.j * G::STRIDE + 1))) & MASK; ok = true; done = true; }
+      else base += N;
+    }
+  }
+}
+
+// One ply with the repetition rule.  Same steps as go_step_kernel; in addition the key of the position after the
+// move is looked up in the game's table before the move is accepted.
+template <int N, bool TIGHT>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint2* zcur) {
+  using G = Geo<N>;
+  __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
+  __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
+  __shared__ uint2 lut[256];
+  const int wib = threadIdx.x >> 6;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  const size_t rows_total = (size_t)a.B * N;
+  Row<N> R;
+  load_row<N>(a.planes, rows_total, L, R);
+  const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
+  const int act = L.boardok ? a.actions[L.b] : -1;
+  const uint2 hcur = L.boardok ? zcur[L.b] : make_uint2(0u, 0u);
+  fill_spread_table(lut);
+  if (wave * G::W >= a.B) return;
+  const Row<N> R_loaded = R;
+  Meta m = unpack_meta(meta_raw);
+  const Meta m_loaded = m;
+  uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
+
+  const bool skip = !L.boardok || act == -1;
+  const bool in_range = act >= 0 && act < G::P;
+  const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
+  const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
+
+  // The key of the position after the move = current key ^ key of the new stone ^ keys of the captured stones.
+  // Most moves capture nothing, so the table is read at the home slot of the first two terms before the rules run
+  // (the loads fly meanwhile) and read again only where stones were taken.
+  constexpr uint32_t ZMASK = Zt<N>::SLOTS - 1u;
+  const bool played = mv.playing;   // a pass shows no new position
+  const uint2 kp = zkey((uint32_t)(played ? mv.pr * N + mv.pc : 0), (uint32_t)m.wtm);
+  const uint2 hpred = make_uint2(hcur.x ^ kp.x, hcur.y ^ kp.y);
+  const uint32_t pre_base = hpred.x & ZMASK;
+  uint2 pre_e = make_uint2(1u, 1u);
+  if (played && L.valid) pre_e = tab[(pre_base + (uint32_t)L.r) & ZMASK];
+
+  // the move is applied (captures included, no reset yet), then the new position is looked up
+  Rules r0 = a.rules;
+  r0.auto_reset = 0;
+  float rew0, rew1;
+  bool flag, reset;
+  uint32_t captured;
+  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
+  const uint32_t gone_b = played ? (R_loaded.bk & ~R.bk) : 0u, gone_w = played ? (R_loaded.wt & ~R.wt) : 0u;
+  uint2 d = make_uint2(0u, 0u);
+  if (__ballot((gone_b | gone_w) != 0u) != 0ull) d = board_xor<N>(L, row_keys<N>(L.r, gone_b, gone_w), lds_mask_all[wib]);
+  const uint2 hnew = make_uint2(hpred.x ^ d.x, hpred.y ^ d.y);
+  bool found, ok;
+  uint32_t free_slot;
+  table_probe<N>(L, tab, zstored(hnew), played, pre_base, pre_e, found, ok, free_slot);
+  const bool violate = played && found;
+  if (__ballot(violate) != 0ull) {   // rare: redo the ply of this wavefront's boards with the offending moves turned illegal
+    R = R_loaded;
+    m = m_loaded;
+    Move mv2 = mv;
+    if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
+    apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
+  }
+  if (!skip && L.valid && L.r == 0) {
+    *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
+    a.term[L.b] = (uint8_t)(flag ? 1 : 0);
+  }
+  // a8: auto-reset, here instead of inside apply_move; the game's table is cleared by the whole wavefront
+  const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
+  if (played && !violate && !do_reset && ok && L.valid && L.r == 0) {
+    tab[free_slot] = zstored(hnew);
+    zcur[L.b] = hnew;
+  }
+  if (do_reset) reset_board<N>(L, R, m, a.rules.seed);
+  for (uint64_t q = __ballot(do_reset && L.valid && L.r == 0); q; q &= q - 1ull) {
+    const int jb = (__ffsll((long long)q) - 1) / G::STRIDE;
+    const size_t bb = (size_t)wave * G::W + jb;
+    uint4* t4 = (uint4*)(zt + bb * Zt<N>::SLOTS);
+    for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) t4[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (L.lane == 0) zcur[bb] = make_uint2(0u, 0u);
+  }
+
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if (!skip) {
+    if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
+    else store_row<N>(a.planes, rows_total, L, R);
+    if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+  }
+  if (a.next_actions) {
+    const bool wait = L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
+    const Draw<N> dr = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
+    if (L.valid && L.r == 0) a.next_actions[L.b] = dr.action();
+  }
+}
+
+// Fills the tables from what the state still carries: the 8 history positions and the current one (set-up, import).
+// The tables must have been cleared by an earlier launch.
+template <int N>
+__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, int B, uint2* zt, uint2* zcur) {
+  __shared__ uint32_t scratch[64];
+  const Lane<N> L(blockIdx.x, threadIdx.x, B);
+  Row<N> R;
+  load_row<N>(planes, (size_t)B * N, L, R);
+  uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
+  for (int i = 8; i >= 0; --i) {   // history position i-1 (oldest first), then i = 0: the current stones
+    uint32_t black = R.bk, white = R.wt;
+    if (i > 0) {
+      black = 0u; white = 0u;
+#pragma unroll
+      for (int col = 0; col < N; ++col) {
+        const uint32_t hw = (R.h[col >> 1] >> ((col & 1) * 16)) & 0xFFFFu;
+        black |= ((hw >> (2 * (i - 1))) & 1u) << col;
+        white |= ((hw >> (2 * (i - 1) + 1)) & 1u) << col;
+      }
+    }
+    uint2 k = make_uint2(0u, 0u);
+    if (L.valid) k = row_keys<N>(L.r, black, white);
+    k = board_xor<N>(L, k, scratch);
+    bool found, ok;
+    uint32_t free_slot;
+    table_probe<N>(L, tab, zstored(k), L.boardok, ~0u, make_uint2(1u, 1u), found, ok, free_slot);
+    if (L.valid && L.r == 0) {
+      if (!found && ok) tab[free_slot] = zstored(k);
+      if (i == 0) zcur[L.b] = k;
+    }
+    __threadfence();   // the next round's look-ups must see this insert
+  }
+}
+
+__global__ void go_zero_kernel(uint4* p, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1022,6 +1237,8 @@ struct pgxgo_ctx {
   uint8_t* obs_out;
   float* rew_out;
   uint8_t* term_out;
+  uint2* zt;     // positional superko: per-game key tables, or null when the rule is off
+  uint2* zcur;   // key of every game's current position
 };
 
 namespace {
@@ -1070,6 +1287,13 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
   const dim3 grid(blocks_for<N>(h->B)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h);
+  if (h->zt) {
+    if (!sample) a.next_actions = nullptr;
+    if (tight) hipLaunchKernelGGL((go_step_superko_kernel<N, true>), grid, block, 0, h->stream, a, h->zt, h->zcur);
+    else hipLaunchKernelGGL((go_step_superko_kernel<N, false>), grid, block, 0, h->stream, a, h->zt, h->zcur);
+    HIPCHK(hipGetLastError());
+    return PGXGO_OK;
+  }
   if (sample && tight) hipLaunchKernelGGL((go_step_kernel<N, true, true>), grid, block, 0, h->stream, a);
   else if (sample) hipLaunchKernelGGL((go_step_kernel<N, true, false>), grid, block, 0, h->stream, a);
   else if (tight) hipLaunchKernelGGL((go_step_kernel<N, false, true>), grid, block, 0, h->stream, a);
@@ -1114,6 +1338,27 @@ int launch_import(pgxgo_ctx* h, const CanonArgs& c) {
   hipLaunchKernelGGL(go_import_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->rew_out, h->term_out, h->B,
                      c);
   HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+template <int N>
+size_t superko_bytes_for(int B, size_t* off_cur) {
+  size_t o = align_up((size_t)B * Zt<N>::SLOTS * sizeof(uint2), 256);
+  if (off_cur) *off_cur = o;
+  return o + align_up((size_t)B * sizeof(uint2), 256);
+}
+
+// clears the tables, then (rebuild) fills them from the history window of the current state
+template <int N>
+int launch_superko_refresh(pgxgo_ctx* h, bool rebuild) {
+  const size_t n16 = superko_bytes_for<N>(h->B, nullptr) / 16;
+  const unsigned blocks = (unsigned)((n16 + 255) / 256 < 65536 ? (n16 + 255) / 256 : 65536);
+  hipLaunchKernelGGL(go_zero_kernel, dim3(blocks), dim3(256), 0, h->stream, (uint4*)h->zt, n16);
+  HIPCHK(hipGetLastError());
+  if (rebuild) {
+    hipLaunchKernelGGL(go_superko_rebuild_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->B, h->zt, h->zcur);
+    HIPCHK(hipGetLastError());
+  }
   return PGXGO_OK;
 }
 
@@ -1184,6 +1429,10 @@ int pgxgo_reset(pgxgo_t h) {
   if (!h) return PGXGO_EINVAL;
   int rc = DISPATCH_N(h, launch_reset<19>(h, 0), launch_reset<9>(h, 0));
   if (rc != PGXGO_OK) return rc;
+  if (h->zt) {
+    rc = DISPATCH_N(h, launch_superko_refresh<19>(h, false), launch_superko_refresh<9>(h, false));
+    if (rc != PGXGO_OK) return rc;
+  }
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
   return PGXGO_OK;
 }
@@ -1213,7 +1462,7 @@ int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint
 
 int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev, int32_t* actions_dev,
                   float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev) {
-  if (!h || steps < 0 || slices < 1) return PGXGO_EINVAL;
+  if (!h || steps < 0 || slices < 1 || h->zt) return PGXGO_EINVAL;
   if (steps == 0) return PGXGO_OK;
   RolloutArgs a;
   a.planes = h->planes; a.meta = h->meta; a.B = h->B;
@@ -1226,7 +1475,7 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
 
 int pgxgo_step_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* actions_dev, const int32_t* dst_slots_dev,
                      uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
-  if (!h || n < 0 || n > h->B || !src_slots_dev || !dst_slots_dev) return PGXGO_EINVAL;
+  if (!h || n < 0 || n > h->B || !src_slots_dev || !dst_slots_dev || h->zt) return PGXGO_EINVAL;
   if (n == 0) return PGXGO_OK;
   SlotArgs a;
   a.planes = h->planes; a.meta = h->meta; a.pool = h->B; a.n = n; a.src = src_slots_dev; a.dst = dst_slots_dev; a.actions = actions_dev;
@@ -1292,8 +1541,33 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
                  (uint8_t*)terminated_dev, (uint8_t*)black_player_dev, (uint32_t*)episode_dev, nullptr};
   int rc = DISPATCH_N(h, launch_import<19>(h, c), launch_import<9>(h, c));
   if (rc != PGXGO_OK) return rc;
+  if (h->zt) {
+    rc = DISPATCH_N(h, launch_superko_refresh<19>(h, true), launch_superko_refresh<9>(h, true));
+    if (rc != PGXGO_OK) return rc;
+  }
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
   return PGXGO_OK;
+}
+
+size_t pgxgo_superko_bytes(int32_t batch, int32_t board_size) {
+  if (batch <= 0) return 0;
+  if (board_size == 19) return superko_bytes_for<19>(batch, nullptr);
+  if (board_size == 9) return superko_bytes_for<9>(batch, nullptr);
+  return 0;
+}
+
+int pgxgo_enable_superko(pgxgo_t h, void* table_dev, size_t table_bytes) {
+  if (!h) return PGXGO_EINVAL;
+  if (!table_dev) { h->zt = nullptr; h->zcur = nullptr; return PGXGO_OK; }
+  if (((uintptr_t)table_dev & 255u) != 0 || h->max_steps > 2 * h->N * h->N) return PGXGO_EINVAL;
+  size_t off_cur;
+  const size_t need = h->N == 19 ? superko_bytes_for<19>(h->B, &off_cur) : superko_bytes_for<9>(h->B, &off_cur);
+  if (table_bytes < need) return PGXGO_EINVAL;
+  h->zt = (uint2*)table_dev;
+  h->zcur = (uint2*)((uint8_t*)table_dev + off_cur);
+  const int rc = DISPATCH_N(h, launch_superko_refresh<19>(h, true), launch_superko_refresh<9>(h, true));
+  if (rc != PGXGO_OK) { h->zt = nullptr; h->zcur = nullptr; }
+  return rc;
 }
 
 int pgxgo_sync(pgxgo_t h) {

@@ -16,12 +16,15 @@ class Pair:
     ids: the oracle replays only these global environment indices (sampled comparison at large batch);
     None = every environment."""
 
-    def __init__(self, batch, N, seed, auto_reset, ids=None, komi_x2=15, max_steps=0, obs_pitch=0, mask_pitch=0, bind=True, emit_obs=True):
+    def __init__(self, batch, N, seed, auto_reset, ids=None, komi_x2=15, max_steps=0, obs_pitch=0, mask_pitch=0, bind=True, emit_obs=True,
+                 superko=False):
         self.B, self.N, self.P = batch, N, N * N
         self.env = pg.GoEnv(batch, N, seed=seed, komi_x2=komi_x2, max_steps=max_steps, auto_reset=auto_reset, obs_pitch=obs_pitch, mask_pitch=mask_pitch)
         self.ids = None if ids is None else np.asarray(ids, np.int32)
         nb = batch if ids is None else len(ids)
-        self.orc = oracle.GoOracle(nb, N, seed=seed, komi_x2=komi_x2, max_steps=max_steps, auto_reset=auto_reset, env_ids=self.ids)
+        self.orc = oracle.GoOracle(nb, N, seed=seed, komi_x2=komi_x2, max_steps=max_steps, auto_reset=auto_reset, env_ids=self.ids, superko=superko)
+        if superko:
+            self.env.enable_superko()
         self.sel = None if ids is None else torch.as_tensor(self.ids.astype(np.int64), device="cuda")
         self.bound = bind
         self.n_compared = 0      # environment-plies whose outputs were compared

@@ -86,3 +86,20 @@ def test_workload_hash_matches_oracle_hash():
     assert st.shape == (65536,) and st.min() == 0 and st.max() == 300
     assert abs(st.mean() - 150) < 2
     assert workloads.start_times(workloads.CONFIGS[3]) is None
+
+
+def test_superko_entry_points_and_key_table():
+    L = pg.lib()
+    assert L.pgxgo_superko_bytes(0, 19) == 0 and L.pgxgo_superko_bytes(4, 13) == 0
+    assert L.pgxgo_superko_bytes(100, 19) >= 100 * (2048 * 8 + 8) and L.pgxgo_superko_bytes(100, 9) >= 100 * (512 * 8 + 8)
+    assert L.pgxgo_enable_superko(None, None, 0) == -1
+    # the position keys are one 64-bit word per (point, colour); their low halves must all differ, or two stones could cancel
+    M = 0xFFFFFFFF
+
+    def mix(x):
+        x ^= x >> 16; x = (x * 0x7feb352d) & M
+        x ^= x >> 15; x = (x * 0x846ca68b) & M
+        return x ^ (x >> 16)
+
+    lows = [mix((0x9E3779B9 * (2 * p + c + 1)) & M) for p in range(361) for c in range(2)]
+    assert len(set(lows)) == 722 and 0 not in lows
