@@ -6,7 +6,7 @@ game, apply it (legality gate, placement, capture, ko, history, termination + ar
 emit the next legal mask [B][362], observation [B][19][19][17], rewards and terminated flags.  The default
 workload is the headline configuration: 19x19, 16384 games, seed 3, auto-reset, 2000 plies per game.
 
-Prints ONE JSON line (see README for the fields).  Inputs are synthetic by construction: the
+Prints ONE JSON line.  Inputs are synthetic by construction: the
 paper's own benchmark is random play from the empty board (Sec. 4.1).
 """
 import argparse
