@@ -7,8 +7,8 @@
 // komi added to White's score, 2x8 history planes + one colour plane, the last
 // action is pass, rewards +1/-1/0).  Where the paper is silent (simple ko,
 // suicide illegal, ply cap 2*N*N, illegal action ends the game, counter-based
-// action sampler) the readings are the ones this repository's design document
-// lists; every one of them is restated next to the code that implements it.
+// action sampler, positional superko as an option) each reading is stated next to
+// the code that implements it.
 //
 // Only tests, the smoke check and the CPU-baseline leg of the benchmark may use
 // this file.  It shares no code, header, table or helper with the HIP library.
