@@ -259,7 +259,7 @@ def bench_hex(args, cfg):
 
     import paper_2303_17503_amd as pg
 
-    assert args.mode == "fused", "--game hex has the fused mode only"
+    assert args.mode in ("fused", "rollout"), "--game hex has the fused and rollout modes"
     B, seed, K, Wm = cfg.batch, cfg.seed, args.steps, args.warmup
     with_obs = not args.no_obs
     env = pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
@@ -268,32 +268,49 @@ def bench_hex(args, cfg):
     rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
     term = torch.zeros(B, dtype=torch.uint8, device="cuda")
     env.bind_outputs(mask, obs, rew, term)
-    acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
-    env.random_actions(seed, 0, out=acts[0])
-    for t in range(Wm):
-        env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for t in range(Wm, Wm + K):
-        env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
-    ev1.record()
-    torch.cuda.synchronize()
+    if args.mode == "rollout":
+        Lr = args.rollout_len
+        assert K % Lr == 0, "--steps must be a multiple of --rollout-len"
+        bufs = dict(actions=torch.empty((1, B), dtype=torch.int32, device="cuda"), rewards=rew.view(1, B, 2), terminated=term.view(1, B),
+                    mask=mask.view(1, B, 122), obs=None if obs is None else obs.view(1, B, 484))
+        if Wm:
+            env.rollout(Wm, seed, 0, **bufs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for i in range(K // Lr):
+            env.rollout(Lr, seed, Wm + i * Lr, **bufs)
+        ev1.record()
+        torch.cuda.synchronize()
+        kname = "hex_rollout_kernel"
+    else:
+        acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
+        env.random_actions(seed, 0, out=acts[0])
+        for t in range(Wm):
+            env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for t in range(Wm, Wm + K):
+            env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
+        ev1.record()
+        torch.cuda.synchronize()
+        kname = "hex_step_kernel<true>"
     wall = time.perf_counter() - t0
-    kern_ms = ev0.elapsed_time(ev1) / K
+    kern_ms = ev0.elapsed_time(ev1) / K       # per ply (a rollout launch covers rollout_len plies)
     copy_gbs = device_copy_gbs(B * (484 + 122))
     bytes_ply = hex_bytes_per_ply(with_obs)
     achieved = bytes_ply * B / (kern_ms * 1e-3) / 1e9
-    traffic = read_traffic(os.path.join(ROOT, "profiles", f"hex_step_kernel_{cfg.name}_pmc.txt")) if with_obs else None
+    traffic = read_traffic(os.path.join(ROOT, "profiles", f"hex_step_kernel_{cfg.name}_pmc.txt")) if with_obs and args.mode == "fused" else None
     out = {
         "metric": "Hex env steps/sec on 1 MI355X (11x11, random legal play); HBM GB/s % peak",
         "value": B * K / wall, "unit": "env steps/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": wall / K * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
         "config": {"workload": cfg.name, "board_size": 11, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset, "observation": with_obs,
-                   "mode": "fused"},
+                   "mode": args.mode, **({"rollout_len": args.rollout_len} if args.mode == "rollout" else {})},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "kernel": "hex_step_kernel<true>", "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
+                     "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
     }
     if not args.no_cpu_baseline:

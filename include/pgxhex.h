@@ -83,6 +83,18 @@ int pgxhex_random_actions(pgxhex_t h, uint32_t seed, uint32_t t, const int32_t* 
 int pgxhex_step_sample(pgxhex_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev,
                        int32_t* next_actions_dev);
 
+/* `steps` plies of uniform random legal play in ONE kernel launch (Sec. 2: all-on-device loops; Sec. 4.1: random
+ * policy with auto-reset).  Exactly equivalent to
+ *   for i in 0..steps-1: pgxhex_random_actions(seed, t0+i, start_t_dev, a); pgxhex_step(a)
+ * but the game state stays in registers between plies.  The outputs of ply i go to slice (i mod slices) of the
+ * caller's trajectory buffers, each of which may be NULL: actions_dev [slices][batch] int32, rewards_dev
+ * [slices][batch][2] float32, terminated_dev [slices][batch] uint8, mask_dev [slices][batch][122],
+ * obs_dev [slices][batch][484] (mask and observation are those AFTER the ply; an environment that still waits for
+ * its start time reports action -1, zero rewards and terminated 0).  Buffers bound with pgxhex_bind_outputs are
+ * not touched. */
+int pgxhex_rollout(pgxhex_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev,
+                   int32_t* actions_dev, float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev);
+
 /* Getters for the current state; each enqueues one kernel or copy into the caller's buffer. */
 int pgxhex_legal_mask(pgxhex_t h, uint8_t* dst_dev /* [batch][122] */);
 int pgxhex_observe(pgxhex_t h, uint8_t* dst_dev /* [batch][484] */);

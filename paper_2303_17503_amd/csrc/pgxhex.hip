@@ -14,6 +14,7 @@
 // sides.  Mask and observation bytes are staged as a bit stream in LDS (4 bits per cell for the observation) and
 // written as aligned 16-byte vectors; the boards of a wavefront form one contiguous run of bytes.
 #include <hip/hip_runtime.h>
+#include <limits.h>
 #include <stdint.h>
 #include <stdlib.h>
 
@@ -194,24 +195,16 @@ struct StepArgs {
   int32_t* next_actions;     // SAMPLE only
 };
 
-// One ply of every game (Fig. 2 "step"): a1 decode, a2 legality gate, a3 placement or swap, a4 winner test,
-// a5 rewards / termination / auto-reset, a6 legal mask, a7 observation, a8 state store, optionally the next draw.
-template <bool SAMPLE>
-__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs a) {
-  __shared__ uint2 lut[256];
-  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
-  __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
-  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
-  const Lane L(wave, lane, a.B);
-  const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
-  const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
-  const int act = L.boardok ? a.actions[L.b] : -1;
-  fill_spread_table(lut);
-  if (wave * W >= a.B) return;
+// What one ply did to a board (the same in every lane of the board)
+struct Ply {
+  bool skip, frozen, ended;
+  float rew0, rew1;     // by player id; zero unless the ply ended the game
+};
 
-  uint32_t bk = word & 0xFFFFu, wt = word >> 16;
-  Meta m = unpack_meta(mv);
+// One ply of every board of the wavefront, registers in, registers out (Fig. 2 "step"): a1 decode, a2 legality
+// gate, a3 placement or swap, a4 winner test, a5 rewards / termination / auto-reset.
+__device__ __forceinline__ Ply hex_ply(const Lane& L, uint32_t& bk, uint32_t& wt, Meta& m, int act, uint32_t seed, int auto_reset) {
+  Ply out;
   const bool skip = act == -1 || !L.boardok;
   const bool frozen = !skip && m.term;        // finished earlier and not reset: nothing changes
   const bool live = !skip && !frozen;
@@ -267,16 +260,39 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   const float r_other = won ? -1.f : (illegal_now ? 1.f : 0.f);
   m.illegal += illegal_now ? 1u : 0u;
   m.term = (m.term || ended) ? 1 : 0;
-  if (ended && a.auto_reset) {   // Sec. 4.1: back to the initial state within the same ply
+  if (ended && auto_reset) {   // Sec. 4.1: back to the initial state within the same ply
     m.episode += 1u;
     bk = 0u; wt = 0u;
     m.steps = 0; m.wtm = 0; m.term = 0;
-    m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)L.b, m.episode) & 1u);
+    m.bp = (int)(env_hash(seed, 1u, (uint32_t)L.b, m.episode) & 1u);
   }
-  if (L.valid && L.r == 0 && !skip) {
-    a.rew[2 * (size_t)L.b + mover] = r_mover;
-    a.rew[2 * (size_t)L.b + 1 - mover] = r_other;
-    a.term[L.b] = (ended || frozen) ? 1 : 0;
+  out.skip = skip; out.frozen = frozen; out.ended = ended;
+  out.rew0 = mover == 0 ? r_mover : r_other;
+  out.rew1 = mover == 0 ? r_other : r_mover;
+  return out;
+}
+
+// One launch = one ply of every game, then a6 legal mask, a7 observation, a8 state store, optionally the next draw.
+template <bool SAMPLE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
+  __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const Lane L(wave, lane, a.B);
+  const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
+  const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
+  const int act = L.boardok ? a.actions[L.b] : -1;
+  fill_spread_table(lut);
+  if (wave * W >= a.B) return;
+
+  uint32_t bk = word & 0xFFFFu, wt = word >> 16;
+  Meta m = unpack_meta(mv);
+  const Ply ply = hex_ply(L, bk, wt, m, act, a.seed, a.auto_reset);
+  if (L.valid && L.r == 0 && !ply.skip) {
+    *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(ply.rew0, ply.rew1);
+    a.term[L.b] = (ply.ended || ply.frozen) ? 1 : 0;
     a.meta[L.b] = pack_meta(m);
   }
   const uint32_t word_new = bk | (wt << 16);
@@ -289,6 +305,58 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
     const int next = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = next;
   }
+}
+
+// `steps` plies of uniform random legal play in one launch (Sec. 2: all-on-device loops; Sec. 4.1: random policy with
+// auto-reset).  The state stays in registers; the outputs of ply i go to slice (i mod slices) of the caller's buffers.
+struct RolloutArgs {
+  uint32_t* rows;
+  uint4* meta;
+  int B;
+  uint32_t seed_env;       // the handle's seed (seat draws)
+  int auto_reset;
+  int steps, slices;
+  uint32_t seed, t0;       // sampler
+  const int32_t* start_t;  // nullable
+  int32_t* actions;        // [slices][B] or null
+  float* rew;              // [slices][B][2] or null
+  uint8_t* term;           // [slices][B] or null
+  uint8_t* mask;           // [slices][B][A] or null
+  uint8_t* obs;            // [slices][B][OBS] or null
+};
+
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_kernel(RolloutArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
+  __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
+  fill_spread_table(lut);
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  if (wave * W >= a.B) return;
+  const Lane L(wave, lane, a.B);
+  const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
+  uint32_t bk = word & 0xFFFFu, wt = word >> 16;
+  Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u));
+  const int64_t start = (L.boardok && a.start_t) ? (int64_t)a.start_t[L.b] : INT64_MIN;
+  int slice = 0;
+  for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
+    const uint32_t t = a.t0 + (uint32_t)i;
+    const bool wait = (int64_t)t < start;
+    const int act = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.seed, t, wait);
+    const Ply ply = hex_ply(L, bk, wt, m, L.boardok ? act : -1, a.seed_env, a.auto_reset);
+    const size_t sb = (size_t)slice * a.B;
+    if (L.valid && L.r == 0) {
+      const size_t e = sb + L.b;
+      if (a.actions) a.actions[e] = act;
+      // a waiting environment reports what a skipped step leaves behind at the start: zeros
+      if (a.rew) *(float2*)(a.rew + 2 * e) = ply.skip ? make_float2(0.f, 0.f) : make_float2(ply.rew0, ply.rew1);
+      if (a.term) a.term[e] = (uint8_t)((!ply.skip && (ply.ended || ply.frozen)) ? 1 : 0);
+    }
+    emit_outputs(L, bk, wt, m, wave, a.B, a.mask ? a.mask + sb * A : nullptr, a.obs ? a.obs + sb * OBS : nullptr, lds_mask[wib], lds_obs[wib], lut);
+    slice = slice + 1 == a.slices ? 0 : slice + 1;
+  }
+  if (L.valid) a.rows[(size_t)L.b * N + L.r] = bk | (wt << 16);
+  if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
 }
 
 __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uint32_t* rows, const uint4* meta, int B, uint8_t* mask, uint8_t* obs) {
@@ -514,6 +582,19 @@ int pgxhex_step(pgxhex_t h, const int32_t* actions_dev) {
 int pgxhex_step_sample(pgxhex_t h, const int32_t* actions_dev, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* next_actions_dev) {
   if (!h || !actions_dev || !next_actions_dev || next_actions_dev == actions_dev) return PGXHEX_EINVAL;
   return launch_step(h, actions_dev, true, seed, t, start_t_dev, next_actions_dev);
+}
+
+int pgxhex_rollout(pgxhex_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev, int32_t* actions_dev,
+                   float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev) {
+  if (!h || steps < 0 || slices < 1) return PGXHEX_EINVAL;
+  if (steps == 0) return PGXHEX_OK;
+  RolloutArgs a;
+  a.rows = h->rows; a.meta = h->meta; a.B = h->B; a.seed_env = h->seed; a.auto_reset = h->auto_reset;
+  a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
+  a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
+  hipLaunchKernelGGL(hex_rollout_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  HIPCHK(hipGetLastError());
+  return PGXHEX_OK;
 }
 
 int pgxhex_random_actions(pgxhex_t h, uint32_t seed, uint32_t t, const int32_t* start_t_dev, int32_t* actions_dev) {

@@ -28,6 +28,7 @@ def lib():
         L.pgxhex_step.argtypes = [vp, vp]
         L.pgxhex_random_actions.argtypes = [vp, u32, u32, vp, vp]
         L.pgxhex_step_sample.argtypes = [vp, vp, u32, u32, vp, vp]
+        L.pgxhex_rollout.argtypes = [vp, i32, i32, u32, u32, vp, vp, vp, vp, vp, vp]
         for n in ("legal_mask", "observe", "rewards", "terminated", "current_player"):
             getattr(L, "pgxhex_" + n).argtypes = [vp, vp]
         L.pgxhex_export_state.argtypes = [vp] * 8
@@ -111,6 +112,18 @@ class HexEnv:
         if start_t is not None: _need(start_t, torch.int32, (self.B,), "start_t")
         _check(lib().pgxhex_step_sample(self._h, _ptr(actions), seed & 0xFFFFFFFF, t & 0xFFFFFFFF, _ptr(start_t), _ptr(out)), "pgxhex_step_sample")
         return out
+
+    def rollout(self, steps, seed, t0, start_t=None, slices=1, actions=None, rewards=None, terminated=None, mask=None, obs=None):
+        """`steps` plies of random legal play in one launch; ply i writes slice i % slices of the given buffers."""
+        S = int(slices)
+        if actions is not None: _need(actions, torch.int32, (S, self.B), "actions")
+        if rewards is not None: _need(rewards, torch.float32, (S, self.B, 2), "rewards")
+        if terminated is not None: _need(terminated, torch.uint8, (S, self.B), "terminated")
+        if mask is not None: _need(mask, torch.uint8, (S, self.B, A), "mask")
+        if obs is not None: _need(obs, torch.uint8, (S, self.B, OBS), "obs")
+        if start_t is not None: _need(start_t, torch.int32, (self.B,), "start_t")
+        _check(lib().pgxhex_rollout(self._h, int(steps), S, seed & 0xFFFFFFFF, t0 & 0xFFFFFFFF, _ptr(start_t), _ptr(actions), _ptr(rewards),
+                                    _ptr(terminated), _ptr(mask), _ptr(obs)), "pgxhex_rollout")
 
     def _get(self, name, shape, dtype, out):
         out = torch.empty(shape, dtype=dtype, device=self.device) if out is None else _need(out, dtype, shape, name)

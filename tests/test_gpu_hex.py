@@ -35,15 +35,18 @@ class HexPair:
     def pick(self, t):
         return to_np(t if self.sel is None else t.index_select(0, self.sel))
 
-    def compare(self, tag="", state=True):
+    def compare(self, tag="", state=True, last_step=True):
+        """last_step=False: skip the rewards / terminated values of the last step call (the rollout kernel reports them in its
+        trajectory buffers only)."""
         e, o = self.env, self.orc
         self.n_compared += o.B
         mask = self.mask if self.bound else e.legal_mask()
         obs = self.obs if self.bound else e.observe()
         assert (self.pick(mask) == o.legal_mask()).all(), f"mask {tag}"
         assert (self.pick(obs).reshape(-1, N, N, 4) == o.observe()).all(), f"observation {tag}"
-        assert (self.pick(self.rew if self.bound else e.rewards()) == o.rewards()).all(), f"rewards {tag}"
-        assert (self.pick(self.term if self.bound else e.terminated()) == o.terminated()).all(), f"terminated {tag}"
+        if last_step:
+            assert (self.pick(self.rew if self.bound else e.rewards()) == o.rewards()).all(), f"rewards {tag}"
+            assert (self.pick(self.term if self.bound else e.terminated()) == o.terminated()).all(), f"terminated {tag}"
         assert (self.pick(e.current_player()) == o.current_player()).all(), f"current player {tag}"
         if state:
             g, c = e.export_state(), o.export_state()
@@ -235,3 +238,52 @@ def test_full_size_configurations(k):
     p.rollout(cfg.seed, 0, plies, fused=True, state_every=50)
     whole_batch_properties(p.env, p.mask, p.obs)
     assert p.n_compared == (cfg.batch if ids is None else len(ids)) * plies
+
+
+def alloc_traj(S, B):
+    return dict(actions=torch.empty((S, B), dtype=torch.int32, device="cuda"),
+                rewards=torch.empty((S, B, 2), dtype=torch.float32, device="cuda"),
+                terminated=torch.empty((S, B), dtype=torch.uint8, device="cuda"),
+                mask=torch.empty((S, B, A), dtype=torch.uint8, device="cuda"),
+                obs=torch.empty((S, B, OBS), dtype=torch.uint8, device="cuda"))
+
+
+@pytest.mark.parametrize("B,auto_reset,stagger", [(131, True, False), (64, False, False), (77, True, True)])
+def test_rollout_kernel_records_the_trajectory(B, auto_reset, stagger):
+    """One launch of T plies against ply-by-ply oracle stepping: every slice of the recorded trajectory is compared."""
+    seed, T = 31, 140
+    p = HexPair(B, seed=seed, auto_reset=auto_reset, bind=False)
+    start = (np.arange(B) % 23).astype(np.int32) if stagger else None
+    tr = alloc_traj(T, B)
+    p.env.rollout(T, seed, 0, start_t=None if start is None else torch.as_tensor(start, device="cuda"), slices=T, **tr)
+    got = {k: to_np(v) for k, v in tr.items()}
+    for t in range(T):
+        a = p.orc.random_actions(seed, t, start)
+        assert (got["actions"][t] == a).all(), f"action t={t}"
+        p.orc.step(a)
+        live = a >= 0
+        assert (got["mask"][t] == p.orc.legal_mask()).all(), f"mask t={t}"
+        assert (got["obs"][t].reshape(B, N, N, 4) == p.orc.observe()).all(), f"observation t={t}"
+        assert (got["rewards"][t][live] == p.orc.rewards()[live]).all() and (got["rewards"][t][~live] == 0).all(), f"rewards t={t}"
+        assert (got["terminated"][t][live] == p.orc.terminated()[live]).all() and (got["terminated"][t][~live] == 0).all(), f"terminated t={t}"
+    p.compare("state after the launch", last_step=False)
+
+
+def test_rollout_kernel_single_slice_full_batch():
+    """The launch shape of bench.py's rollout mode: every ply overwrites one set of buffers; sampled environments."""
+    from paper_2303_17503_amd import workloads
+    cfg = workloads.HEX_CONFIGS[1]
+    ids = np.unique(np.concatenate([[0, 4, 5, cfg.batch - 1], np.random.default_rng(3).integers(0, cfg.batch, 150)]))
+    p = HexPair(cfg.batch, seed=cfg.seed, auto_reset=True, ids=ids, bind=False)
+    tr = alloc_traj(1, cfg.batch)
+    t = 0
+    for L_ in (50, 1, 37, 50):
+        p.env.rollout(L_, cfg.seed, t, slices=1, **tr)
+        for i in range(L_):
+            a = p.orc.random_actions(cfg.seed, t + i)
+            p.orc.step(a)
+        t += L_
+        assert (p.pick(tr["actions"][0]) == a).all()
+        assert (p.pick(tr["mask"][0]) == p.orc.legal_mask()).all() and (p.pick(tr["obs"][0]).reshape(-1, N, N, 4) == p.orc.observe()).all()
+        assert (p.pick(tr["rewards"][0]) == p.orc.rewards()).all() and (p.pick(tr["terminated"][0]) == p.orc.terminated()).all()
+        p.compare(f"after {t} plies", last_step=False)
