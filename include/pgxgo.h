@@ -152,6 +152,12 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
                        const int8_t* to_play_dev, const int32_t* steps_dev, const int8_t* passes_dev,
                        const uint8_t* terminated_dev, const uint8_t* black_player_dev, const uint32_t* episode_dev);
 
+/* Launch-shape knob: how many boards the step and rollout kernels put into one 64-lane wavefront, 1 up to
+ * pgxgo_boards_per_wavefront(board_size).  0 restores the automatic choice made by pgxgo_init (fewer boards per
+ * wavefront for small batches, where latency rather than throughput decides).  Results do not depend on it.
+ * Returns the value now in use (> 0), or a negative error code. */
+int pgxgo_set_boards_per_wavefront(pgxgo_t h, int32_t boards);
+
 /* Positional superko (Appendix C "Go": Tromp-Taylor rules, whose repetition rule forbids a play that recreates an
  * earlier whole-board position of the game).  Off by default (simple ko only).  Reading: the rule is enforced when
  * the move is played -- a play that brings back a position the game has already shown is an illegal action (the

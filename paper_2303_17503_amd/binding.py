@@ -45,6 +45,7 @@ def lib():
         L.pgxgo_export_state.argtypes = [vp] * 11
         L.pgxgo_import_state.argtypes = [vp] * 10
         L.pgxgo_sync.argtypes = [vp]
+        L.pgxgo_set_boards_per_wavefront.argtypes = [vp, i32]
         L.pgxgo_superko_bytes.restype = C.c_size_t
         L.pgxgo_superko_bytes.argtypes = [i32, i32]
         L.pgxgo_enable_superko.argtypes = [vp, vp, C.c_size_t]
@@ -208,6 +209,13 @@ class GoEnv:
 
     def sync(self):
         _check(lib().pgxgo_sync(self._h), "pgxgo_sync")
+
+    def set_boards_per_wavefront(self, boards=0):
+        """Launch-shape knob of the step and rollout kernels (0 = automatic); returns the value in use."""
+        rc = lib().pgxgo_set_boards_per_wavefront(self._h, int(boards))
+        if rc <= 0:
+            _check(rc if rc < 0 else -1, "pgxgo_set_boards_per_wavefront")
+        return rc
 
     def enable_superko(self, on=True):
         """Positional superko: a play that recreates an earlier position of the game becomes an illegal action."""

@@ -142,17 +142,18 @@ struct Lane {
   bool boardok;          // slot j holds a real board (also true for its sentinel lane)
   uint32_t seglo, seghi; // lanes of the rows of this lane's board
   uint32_t full;         // FULL on valid lanes, else 0
-  __device__ __forceinline__ Lane(int wave, int lane_, int B) {
+  // wb: boards this launch puts into a wavefront (1 .. W; fewer than W trades lanes for latency at small batches)
+  __device__ __forceinline__ Lane(int wave, int lane_, int B, int wb = Geo<N>::W) {
     using G = Geo<N>;
     lane = lane_;
     j = lane / G::STRIDE;
     int rr = lane - j * G::STRIDE;
     r = rr - 1;
-    b = wave * G::W + j;
+    b = wave * wb + j;
     slot = b;
-    boardok = (j < G::W) && (b < B);
+    boardok = (j < wb) && (b < B);
     valid = boardok && rr >= 1;
-    uint64_t seg = (j < G::W) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
+    uint64_t seg = (j < wb) ? (((1ull << N) - 1ull) << (j * G::STRIDE + 1)) : 0ull;
     seglo = (uint32_t)seg; seghi = (uint32_t)(seg >> 32);
     full = valid ? G::FULL : 0u;
   }
@@ -245,12 +246,12 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
 // one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
-                                          uint32_t* lds_mask, const uint2* lut) {
+                                          uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
   static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
   constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1
-  const int b0 = wave * G::W;
-  const int nb = B - b0 < G::W ? B - b0 : G::W;   // boards of this wavefront
+  const int b0 = wave * wb;
+  const int nb = B - b0 < wb ? B - b0 : wb;   // boards of this wavefront
   lds_mask[L.lane] = 0u;
   wave_lds_fence();
   if (L.valid) {
@@ -277,12 +278,12 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
 // Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
-                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut) {
+                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
   static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
   constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17
-  const int b0 = wave * G::W;
-  const int nb = B - b0 < G::W ? B - b0 : G::W;
+  const int b0 = wave * wb;
+  const int nb = B - b0 < wb ? B - b0 : wb;
   // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
   // then the colour bit (Appendix C "Go", Observation); a row is N such pieces back to back.
   uint32_t S[G::NR];
@@ -341,9 +342,9 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
-                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut) {
-  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut);
-  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut);
+                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
+  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
+  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -616,6 +617,7 @@ struct StepArgs {
   uint8_t* obs;
   int64_t mask_pitch, obs_pitch;
   int B;
+  int wb;                    // boards per wavefront of this launch
   int sparse_store;
   Rules rules;
   // fused sampler
@@ -632,7 +634,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   __shared__ uint2 lut[256];
   const int wib = threadIdx.x >> 6;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
-  const Lane<N> L(wave, threadIdx.x & 63, a.B);   // in a wavefront beyond the batch no lane is valid
+  const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);   // in a wavefront beyond the batch no lane is valid
   const size_t rows_total = (size_t)a.B * N;
 
   // the loads are issued first and fly while the block fills its lookup table
@@ -641,7 +643,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
   fill_spread_table(lut);
-  if (wave * G::W >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
+  if (wave * a.wb >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
   const Row<N> R_loaded = R;
   Meta m = unpack_meta(meta_raw);
 
@@ -662,9 +664,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   }
 
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
@@ -768,7 +770,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   __shared__ uint2 lut[256];
   const int wib = threadIdx.x >> 6;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
-  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
   const size_t rows_total = (size_t)a.B * N;
   Row<N> R;
   load_row<N>(a.planes, rows_total, L, R);
@@ -776,7 +778,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   const int act = L.boardok ? a.actions[L.b] : -1;
   const uint2 hcur = L.boardok ? zcur[L.b] : make_uint2(0u, 0u);
   fill_spread_table(lut);
-  if (wave * G::W >= a.B) return;
+  if (wave * a.wb >= a.B) return;
   const Row<N> R_loaded = R;
   Meta m = unpack_meta(meta_raw);
   const Meta m_loaded = m;
@@ -833,15 +835,15 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   if (do_reset) reset_board<N>(L, R, m, a.rules.seed);
   for (uint64_t q = __ballot(do_reset && L.valid && L.r == 0); q; q &= q - 1ull) {
     const int jb = (__ffsll((long long)q) - 1) / G::STRIDE;
-    const size_t bb = (size_t)wave * G::W + jb;
+    const size_t bb = (size_t)wave * a.wb + jb;
     uint4* t4 = (uint4*)(zt + bb * Zt<N>::SLOTS);
     for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) t4[i] = make_uint4(0u, 0u, 0u, 0u);
     if (L.lane == 0) zcur[bb] = make_uint2(0u, 0u);
   }
 
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
   if (!skip) {
     if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
     else store_row<N>(a.planes, rows_total, L, R);
@@ -968,6 +970,7 @@ struct RolloutArgs {
   uint4* planes;
   uint4* meta;
   int B;
+  int wb;               // boards per wavefront of this launch
   Rules rules;
   int steps, slices;
   uint32_t seed, t0;
@@ -989,8 +992,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
   fill_spread_table(lut);
   const int wib = threadIdx.x >> 6;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
-  if (wave * G::W >= a.B) return;
-  const Lane<N> L(wave, threadIdx.x & 63, a.B);
+  if (wave * a.wb >= a.B) return;
+  const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
   const size_t rows_total = (size_t)a.B * N;
 
   Row<N> R;
@@ -1017,7 +1020,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
     emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
-                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
+                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
   }
@@ -1225,6 +1228,7 @@ size_t state_bytes_for(int B, size_t* off_meta, size_t* off_rew, size_t* off_ter
 
 struct pgxgo_ctx {
   int B, N;
+  int wb;        // boards per wavefront used by the step and rollout launches (1 .. W)
   uint32_t seed;
   int komi_x2, max_steps, auto_reset;
   int64_t obs_pitch, mask_pitch;
@@ -1258,6 +1262,16 @@ template <int N>
 unsigned waves_for(int B) { return (unsigned)((B + Geo<N>::W - 1) / Geo<N>::W); }
 template <int N>
 unsigned blocks_for(int B) { return (waves_for<N>(B) + kWavesPerBlock - 1) / kWavesPerBlock; }
+unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + kWavesPerBlock - 1) / kWavesPerBlock; }
+
+// Boards per wavefront for the step and rollout launches.  A wavefront can hold W boards; with few games it is
+// better to spread them over more wavefronts (shorter floods, fewer output rounds per wavefront), so the count
+// grows with the batch until about two wavefronts per SIMD exist.
+template <int N>
+int auto_boards_per_wavefront(int B) {
+  const int want = (B + 2047) / 2048;
+  return want < 1 ? 1 : (want > Geo<N>::W ? Geo<N>::W : want);
+}
 
 // both output pitches are the tight ones: the kernels may treat a wavefront's boards as one run of bytes
 template <int N>
@@ -1280,12 +1294,12 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   StepArgs a;
   a.planes = h->planes; a.meta = h->meta; a.actions = actions; a.rew = h->rew_out; a.term = h->term_out;
   a.mask = h->mask_out; a.obs = h->obs_out; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
-  a.B = h->B; a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
+  a.B = h->B; a.wb = h->wb; a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
   // bytes one ply touches: state rows + outputs; 256 MB of memory-side cache on this part, keep a margin
   const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
-  const dim3 grid(blocks_for<N>(h->B)), block(64 * kWavesPerBlock);
+  const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
     if (!sample) a.next_actions = nullptr;
@@ -1312,8 +1326,8 @@ int launch_random(pgxgo_ctx* h, uint32_t seed, uint32_t t, const int32_t* start_
 
 template <int N>
 int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
-  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_rollout_kernel<N, true>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
-  else hipLaunchKernelGGL((go_rollout_kernel<N, false>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_rollout_kernel<N, true>), dim3(blocks_for_wb(h->B, h->wb)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  else hipLaunchKernelGGL((go_rollout_kernel<N, false>), dim3(blocks_for_wb(h->B, h->wb)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1400,6 +1414,7 @@ int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, c
   pgxgo_ctx* h = (pgxgo_ctx*)calloc(1, sizeof(pgxgo_ctx));
   if (!h) return PGXGO_ENOMEM;
   h->B = batch; h->N = board_size; h->seed = seed;
+  h->wb = board_size == 19 ? auto_boards_per_wavefront<19>(batch) : auto_boards_per_wavefront<9>(batch);
   h->komi_x2 = o.komi_x2; h->max_steps = o.max_steps; h->auto_reset = o.auto_reset ? 1 : 0;
   h->obs_pitch = o.obs_pitch; h->mask_pitch = o.mask_pitch;
   h->stream = (hipStream_t)o.stream;
@@ -1465,7 +1480,7 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
   if (!h || steps < 0 || slices < 1 || h->zt) return PGXGO_EINVAL;
   if (steps == 0) return PGXGO_OK;
   RolloutArgs a;
-  a.planes = h->planes; a.meta = h->meta; a.B = h->B;
+  a.planes = h->planes; a.meta = h->meta; a.B = h->B; a.wb = h->wb;
   a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
@@ -1547,6 +1562,14 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
   }
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));
   return PGXGO_OK;
+}
+
+int pgxgo_set_boards_per_wavefront(pgxgo_t h, int32_t boards) {
+  if (!h) return PGXGO_EINVAL;
+  const int wmax = h->N == 19 ? Geo<19>::W : Geo<9>::W;
+  if (boards < 0 || boards > wmax) return PGXGO_EINVAL;
+  h->wb = boards ? boards : (h->N == 19 ? auto_boards_per_wavefront<19>(h->B) : auto_boards_per_wavefront<9>(h->B));
+  return h->wb;
 }
 
 size_t pgxgo_superko_bytes(int32_t batch, int32_t board_size) {

@@ -403,3 +403,28 @@ def test_slot_step_and_copy_for_tree_search(N, pool, auto_reset):
                    torch.as_tensor(np.array([3, 4], np.int32), device="cuda"), terminated=term)
     assert to_np(term)[1] == 255
     check_pool("bad slot ignored")
+
+
+@pytest.mark.parametrize("N,wb", [(19, 1), (19, 2), (19, 3), (9, 1), (9, 2), (9, 3), (9, 4), (9, 5), (9, 6)])
+def test_every_launch_shape(N, wb):
+    """The number of boards a wavefront holds is a launch-shape choice: every value gives the oracle's results
+    (ragged last wavefront, step with and without the fused sampler, the rollout kernel, the superko kernel)."""
+    import paper_2303_17503_amd as pg
+    from gpu_common import Pair, to_np
+    B, seed = 6 * wb + (wb + 1) // 2 + 11, 40 + wb
+    p = Pair(B, N, seed=seed, auto_reset=True)
+    assert p.env.set_boards_per_wavefront(wb) == wb
+    p.rollout(seed, 0, 60, fused=False, state_every=10)
+    p.rollout(seed, 60, 140, fused=True, state_every=20)
+    # rollout kernel: 35 plies in one launch, then compare the state
+    p.env.rollout(35, seed, 140)
+    for t in range(140, 175):
+        p.orc.step(p.orc.random_actions(seed, t))
+    g, c = p.env.export_state(), p.orc.export_state()
+    assert (to_np(g["board"]) == c.board).all() and (to_np(g["history"]) == c.history).all() and (to_np(g["steps"]) == c.steps).all()
+    q = Pair(B, N, seed=seed, auto_reset=True, superko=True)
+    q.env.set_boards_per_wavefront(wb)
+    q.rollout(seed, 0, 90, fused=True, state_every=30)
+    with pytest.raises(pg.PgxGoError):
+        p.env.set_boards_per_wavefront(7)
+    assert p.env.set_boards_per_wavefront(0) == 1            # automatic choice for a batch this small
