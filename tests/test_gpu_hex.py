@@ -287,3 +287,18 @@ def test_rollout_kernel_single_slice_full_batch():
         assert (p.pick(tr["mask"][0]) == p.orc.legal_mask()).all() and (p.pick(tr["obs"][0]).reshape(-1, N, N, 4) == p.orc.observe()).all()
         assert (p.pick(tr["rewards"][0]) == p.orc.rewards()).all() and (p.pick(tr["terminated"][0]) == p.orc.terminated()).all()
         p.compare(f"after {t} plies", last_step=False)
+
+
+@pytest.mark.parametrize("B", [1, 2, 6])
+def test_tiny_batches(B):
+    p = HexPair(B, seed=80 + B, auto_reset=True)
+    p.rollout(80 + B, 0, 300, fused=True, state_every=20)
+    assert to_np(p.env.export_state()["episode"]).min() >= 1
+    q = HexPair(B, seed=81, auto_reset=True, bind=False)
+    tr = alloc_traj(1, B)
+    q.env.rollout(130, 81, 0, slices=1, **tr)
+    for t in range(130):
+        a = q.orc.random_actions(81, t)
+        q.orc.step(a)
+    assert (to_np(tr["actions"][0]) == a).all() and (to_np(tr["mask"][0]) == q.orc.legal_mask()).all()
+    q.compare("after the launch", last_step=False)

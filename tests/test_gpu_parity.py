@@ -428,3 +428,20 @@ def test_every_launch_shape(N, wb):
     with pytest.raises(pg.PgxGoError):
         p.env.set_boards_per_wavefront(7)
     assert p.env.set_boards_per_wavefront(0) == 1            # automatic choice for a batch this small
+
+
+@pytest.mark.parametrize("N,B", [(19, 1), (19, 2), (9, 1), (9, 7)])
+def test_tiny_batches(N, B):
+    """A single game (one partly filled wavefront, one block) through every stepping path."""
+    from gpu_common import Pair, to_np
+    p = Pair(B, N, seed=70 + B, auto_reset=True)
+    p.rollout(70 + B, 0, 2 * N * N + 40, fused=True, state_every=25)
+    assert to_np(p.env.export_state()["episode"]).min() >= 1
+    q = Pair(B, N, seed=71, auto_reset=False, superko=True)
+    q.rollout(71, 0, 120, fused=False, state_every=30)
+    r = Pair(B, N, seed=72, auto_reset=True, bind=False)
+    r.env.rollout(90, 72, 0)
+    for t in range(90):
+        r.orc.step(r.orc.random_actions(72, t))
+    g, c = r.env.export_state(), r.orc.export_state()
+    assert (to_np(g["board"]) == c.board).all() and (to_np(g["history"]) == c.history).all() and (to_np(g["ko"]) == c.ko).all()
