@@ -90,7 +90,7 @@ class GoOracle:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # module globals are gone when the interpreter shuts down
             lib().oracle_destroy(h)
 
     def reset(self):

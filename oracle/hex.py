@@ -69,7 +69,7 @@ class HexOracle:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # module globals are gone when the interpreter shuts down
             lib().hexo_destroy(h)
 
     def reset(self):

@@ -103,7 +103,7 @@ class GoEnv:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # module globals are gone when the interpreter shuts down
             lib().pgxgo_destroy(h)
 
     # ---- buffers -------------------------------------------------------------------------------------

@@ -72,7 +72,7 @@ class HexEnv:
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None
-        if h:
+        if h and lib is not None:   # module globals are gone when the interpreter shuts down
             lib().pgxhex_destroy(h)
 
     def new_mask(self):
