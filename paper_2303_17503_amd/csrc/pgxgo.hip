@@ -246,7 +246,7 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
 // one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
-                                          uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W) {
+                                          uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
   using G = Geo<N>;
   static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
   constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1
@@ -266,11 +266,11 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::A / 16 + 63) / 64>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane);
+    emit_bytes<(G::W * G::A / 16 + 63) / 64>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane, nt);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
+      if (jj < nb) emit_bytes<G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane, nt);
   }
   wave_lds_fence();
 }
@@ -278,7 +278,7 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
 // Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
-                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
+                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
   using G = Geo<N>;
   static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
   constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17
@@ -330,11 +330,11 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::OBS / 16 + 63) / 64>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane);
+    emit_bytes<(G::W * G::OBS / 16 + 63) / 64>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane, nt);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
+      if (jj < nb) emit_bytes<G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane, nt);
   }
   wave_lds_fence();
 }
@@ -342,9 +342,9 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
-                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
-  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
-  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
+                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
+  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb, nt);
+  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb, nt);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -618,6 +618,7 @@ struct StepArgs {
   int64_t mask_pitch, obs_pitch;
   int B;
   int wb;                    // boards per wavefront of this launch
+  int nt_store;              // non-temporal output stores (launches that write far more than the memory-side cache holds)
   int sparse_store;
   Rules rules;
   // fused sampler
@@ -664,9 +665,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   }
 
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb, a.nt_store != 0);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
@@ -841,9 +842,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
     if (L.lane == 0) zcur[bb] = make_uint2(0u, 0u);
   }
 
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb, a.nt_store != 0);
   if (!skip) {
     if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
     else store_row<N>(a.planes, rows_total, L, R);
@@ -971,6 +972,7 @@ struct RolloutArgs {
   uint4* meta;
   int B;
   int wb;               // boards per wavefront of this launch
+  int nt_store;         // non-temporal output stores
   Rules rules;
   int steps, slices;
   uint32_t seed, t0;
@@ -1020,7 +1022,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
     emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
-                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
+                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
   }
@@ -1267,6 +1269,14 @@ unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + 
 // Boards per wavefront for the step and rollout launches.  A wavefront can hold W boards; with few games it is
 // better to spread them over more wavefronts (shorter floods, fewer output rounds per wavefront), so the count
 // grows with the batch until about two wavefronts per SIMD exist.
+// Output bytes of one ply from which the vector stores carry the non-temporal hint: measured at 19x19 with the
+// observation, the hint costs 20-30 % up to ~50 k games (everything still fits the 256 MB memory-side cache together
+// with the state) and gains 9-17 % from ~57 k games on.
+constexpr size_t kNonTemporalFrom = (size_t)350 << 20;
+size_t output_bytes_per_ply(const pgxgo_ctx* h, bool with_mask, bool with_obs) {
+  return (size_t)h->B * ((with_mask ? (size_t)h->mask_pitch : 0) + (with_obs ? (size_t)h->obs_pitch : 0));
+}
+
 template <int N>
 int auto_boards_per_wavefront(int B) {
   const int want = (B + 2047) / 2048;
@@ -1299,6 +1309,7 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   // bytes one ply touches: state rows + outputs; 256 MB of memory-side cache on this part, keep a margin
   const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
+  a.nt_store = output_bytes_per_ply(h, h->mask_out != nullptr, h->obs_out != nullptr) > kNonTemporalFrom ? 1 : 0;
   const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
@@ -1481,6 +1492,7 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
   if (steps == 0) return PGXGO_OK;
   RolloutArgs a;
   a.planes = h->planes; a.meta = h->meta; a.B = h->B; a.wb = h->wb;
+  a.nt_store = 0;   // measured: the hint slows the rollout kernel down at every size (96 vs 62 us per ply at 65536 games)
   a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;

@@ -59,8 +59,10 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
   __syncthreads();
 }
 
+// nt (the same for the whole wavefront): store the vectors with the non-temporal hint.  That pays only when a launch
+// writes far more than the memory-side cache holds; below that size it is slower.
 template <int ROUNDS>
-__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane, bool nt = false) {
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
   uint8_t* base = dst - head;
   const uint32_t total = head + nbytes;
@@ -77,7 +79,15 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
 #pragma unroll
     for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
       const uint2 lo = lut[v[i - g] & 255u], hi = lut[v[i - g] >> 8];
-      if (mine + 64u * i < m1) out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+      if (mine + 64u * i < m1) {
+        if (nt) {
+          typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
+          const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
+          __builtin_nontemporal_store(v4, (vec4u*)&out[64 * i]);
+        } else {
+          out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
   }
