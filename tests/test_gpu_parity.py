@@ -445,3 +445,57 @@ def test_tiny_batches(N, B):
         r.orc.step(r.orc.random_actions(72, t))
     g, c = r.env.export_state(), r.orc.export_state()
     assert (to_np(g["board"]) == c.board).all() and (to_np(g["history"]) == c.history).all() and (to_np(g["ko"]) == c.ko).all()
+
+
+@pytest.mark.parametrize("ci,plies", [(3, 420), (4, 380)])
+def test_whole_batch_properties_every_ply(ci, plies):
+    """Facts that hold for every game at any size, checked on the device tensors of the full batch after every ply
+    (the oracle replays only a sample of these batches): pass is legal, legal points are empty, an empty point next to
+    an empty point is legal unless it is the ko point, observation planes against the exported history, the
+    shift-and-swap of the planes from ply to ply, rewards and termination."""
+    import paper_2303_17503_amd as pg
+    cfg = workloads.CONFIGS[ci]
+    B, N, seed = cfg.batch, cfg.board_size, cfg.seed
+    P = N * N
+    env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=True)
+    mask, obs = env.new_mask(), env.new_obs()
+    rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
+    term = torch.zeros(B, dtype=torch.uint8, device="cuda")
+    env.bind_outputs(mask, obs, rew, term)
+    start = workloads.start_times(cfg)
+    st = None if start is None else torch.as_tensor(start, device="cuda")
+    a = env.random_actions(seed, 0, st)
+    prev = None
+    n_term = 0
+    for t in range(plies):
+        a = env.step_sample(a, seed, t + 1, st)
+        o = obs.view(B, N, N, 17)
+        assert bool((mask[:, P] == 1).all()), f"pass legal t={t}"
+        if t % 20 == 0 or t == plies - 1:
+            g = env.export_state()
+            bd = g["board"].view(B, N, N)
+            emp = bd == 0
+            m = mask[:, :P].view(B, N, N) == 1
+            assert bool((m & ~emp).sum() == 0), f"legal points are empty t={t}"
+            nb = torch.zeros_like(emp)
+            nb[:, 1:, :] |= emp[:, :-1, :]; nb[:, :-1, :] |= emp[:, 1:, :]; nb[:, :, 1:] |= emp[:, :, :-1]; nb[:, :, :-1] |= emp[:, :, 1:]
+            ko = torch.zeros((B, P + 1), dtype=torch.bool, device="cuda")
+            ko[torch.arange(B, device="cuda"), torch.where(g["ko"] >= 0, g["ko"], P).long()] = True
+            must = emp & nb & ~ko[:, :P].view(B, N, N)
+            assert bool((must & ~m).sum() == 0), f"an empty point next to an empty point is legal t={t}"
+            mover = g["to_play"].view(B, 1, 1, 1)
+            hist = g["history"].view(B, 8, N, N).permute(0, 2, 3, 1)                      # [B][N][N][8]
+            assert bool((o[..., 0:16:2] == (hist == mover)).all()) and bool((o[..., 1:16:2] == (hist == -mover)).all()), f"planes vs history t={t}"
+            assert bool((o[..., 16] == (g["to_play"] == 1).view(B, 1, 1)).all()), f"colour plane t={t}"
+            assert bool((hist[..., 0] == bd).all()), f"history[0] is the position t={t}"
+        # rewards and termination of this ply
+        fin = term == 1
+        n_term += int(fin.sum())
+        assert bool((rew.sum(1) == 0).all()) and bool((rew[fin].abs() == 1).all()) and bool((rew[~fin] == 0).all()), f"rewards t={t}"
+        moved = (a >= -1) if st is None else (st <= t)          # games already past their start time took part in this ply
+        if prev is not None:
+            keep = ~fin & moved & prev_moved                     # no reset in between: the planes shift by one ply and swap sides
+            assert bool((o[keep][..., 2:16:2] == prev[keep][..., 1:14:2]).all()) and bool((o[keep][..., 3:16:2] == prev[keep][..., 0:14:2]).all()), f"shift t={t}"
+        prev = o.clone()
+        prev_moved = moved if isinstance(moved, torch.Tensor) else torch.ones(B, dtype=torch.bool, device="cuda")
+    assert n_term > 0 or ci == 4
