@@ -66,3 +66,35 @@ def test_go19_step_in_a_graph():
 def test_hex_step_in_a_graph():
     B, seed = 333, 23
     run(lambda: pg.HexEnv(B, seed=seed, auto_reset=True), lambda: hx.HexOracle(B, 11, seed=seed, auto_reset=True), (B, 11, 11, 4), B, seed, replays=8)
+
+
+def test_two_handles_on_two_streams():
+    """Handles share nothing: two batches stepped concurrently on their own streams both follow the oracle."""
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    B1, B2, seed = 300, 500, 31
+    with torch.cuda.stream(s1):
+        e1 = pg.GoEnv(B1, 19, seed=seed, auto_reset=True)
+        m1, o1 = e1.new_mask(), e1.new_obs()
+        e1.bind_outputs(m1, o1, None, None)
+        a1 = e1.random_actions(seed, 0)
+    with torch.cuda.stream(s2):
+        e2 = pg.HexEnv(B2, seed=seed, auto_reset=True)
+        m2, o2 = e2.new_mask(), e2.new_obs()
+        e2.bind_outputs(m2, o2, None, None)
+        a2 = e2.random_actions(seed, 0)
+    c1 = oracle.GoOracle(B1, 19, seed=seed, auto_reset=True)
+    c2 = hx.HexOracle(B2, 11, seed=seed, auto_reset=True)
+    T = 150
+    for t in range(T):                       # no synchronisation inside the loop: the two launch chains overlap freely
+        with torch.cuda.stream(s1):
+            a1 = e1.step_sample(a1, seed, t + 1)
+        with torch.cuda.stream(s2):
+            a2 = e2.step_sample(a2, seed, t + 1)
+    for t in range(T):
+        c1.step(c1.random_actions(seed, t))
+        c2.step(c2.random_actions(seed, t))
+    s1.synchronize(); s2.synchronize()
+    assert (to_np(m1) == c1.legal_mask()).all() and (to_np(o1).reshape(B1, 19, 19, 17) == c1.observe()).all()
+    assert (to_np(a1) == c1.random_actions(seed, T)).all()
+    assert (to_np(m2) == c2.legal_mask()).all() and (to_np(o2).reshape(B2, 11, 11, 4) == c2.observe()).all()
+    assert (to_np(a2) == c2.random_actions(seed, T)).all()
