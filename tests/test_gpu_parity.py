@@ -499,3 +499,38 @@ def test_whole_batch_properties_every_ply(ci, plies):
         prev = o.clone()
         prev_moved = moved if isinstance(moved, torch.Tensor) else torch.ones(B, dtype=torch.bool, device="cuda")
     assert n_term > 0 or ci == 4
+
+
+def test_c_abi_with_default_options():
+    """The boundary used directly (ctypes, no binding class): NULL options select komi 7.5, cap 2*N*N, no auto-reset,
+    tight pitches and the default stream."""
+    import ctypes as C
+    import paper_2303_17503_amd as pg
+    L = pg.lib()
+    B, N = 5, 9
+    nbytes = L.pgxgo_state_bytes(B, N)
+    state = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    h = C.c_void_p()
+    assert L.pgxgo_init(C.byref(h), B, N, 123, None, C.c_void_p(state.data_ptr()), nbytes) == 0
+    try:
+        mask = torch.empty((B, 82), dtype=torch.uint8, device="cuda")
+        rew = torch.empty((B, 2), dtype=torch.float32, device="cuda")
+        term = torch.empty(B, dtype=torch.uint8, device="cuda")
+        cur = torch.empty(B, dtype=torch.uint8, device="cuda")
+        acts = torch.full((B,), 81, dtype=torch.int32, device="cuda")           # everybody passes
+        p = lambda t: C.c_void_p(t.data_ptr())
+        assert L.pgxgo_legal_mask(h, p(mask)) == 0 and L.pgxgo_current_player(h, p(cur)) == 0
+        assert L.pgxgo_sync(h) == 0
+        assert bool((mask == 1).all())
+        black = cur.clone()                                                        # Black moves first: the player to move now holds Black
+        assert L.pgxgo_step(h, p(acts)) == 0 and L.pgxgo_step(h, p(acts)) == 0
+        assert L.pgxgo_rewards(h, p(rew)) == 0 and L.pgxgo_terminated(h, p(term)) == 0 and L.pgxgo_sync(h) == 0
+        assert bool((term == 1).all())                                             # two passes end the game; no auto-reset
+        r = rew.cpu().numpy(); bp = black.cpu().numpy()
+        for b in range(B):                                                         # empty board: White wins by the komi
+            assert r[b, bp[b]] == -1 and r[b, 1 - bp[b]] == 1
+        assert L.pgxgo_step(h, p(acts)) == 0 and L.pgxgo_rewards(h, p(rew)) == 0 and L.pgxgo_sync(h) == 0
+        assert bool((rew == 0).all())                                              # frozen afterwards
+    finally:
+        assert L.pgxgo_destroy(h) == 0
