@@ -28,7 +28,11 @@
 //     keep their history word).
 //   * Kernels: go_step_kernel (one ply per launch, optionally drawing the next random action),
 //     go_rollout_kernel (T plies per launch, state in registers), go_step_slots_kernel (tree search: step
-//     from and to arbitrary state slots), plus small set-up / export / import kernels.
+//     from and to arbitrary state slots), go_step_superko_kernel (one ply with the positional-superko rule:
+//     Zobrist keys in per-game open-addressing tables), plus small set-up / export / import kernels.
+//   * How many boards a launch puts into a wavefront (1 .. W) is chosen per launch: W for throughput at large
+//     batches, fewer at small batches where the slowest board of a wavefront and its serial output rounds
+//     decide the latency.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
