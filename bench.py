@@ -199,12 +199,19 @@ def main():
         env.random_actions(seed, 0, start_dev, out=acts[0])
         run_steps(0, pre + Wm)
         torch.cuda.synchronize()
+        # the timed region, cut into five segments by events on the same stream (median and best segment are reported too)
+        cuts = [K * i // 5 for i in range(6)]
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         t0 = time.perf_counter()
         ev0.record()
-        run_steps(pre + Wm, K)
+        for i in range(5):
+            run_steps(pre + Wm + cuts[i], cuts[i + 1] - cuts[i])
+            if i < 4: marks[i].record()
         ev1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        evs = [ev0] + marks + [ev1]
+        seg_ms = [evs[i].elapsed_time(evs[i + 1]) / max(1, cuts[i + 1] - cuts[i]) for i in range(5)] if K >= 5 else []
         if args.mode == "fused":
             # the timed region is K launches of the one kernel, back to back on the stream the events are on
             kern_ms = ev0.elapsed_time(ev1) / K
@@ -241,6 +248,10 @@ def main():
                      "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
     }
+    if args.mode == "fused" and seg_ms:
+        out["roofline"]["kernel_ms_segments"] = seg_ms
+        out["roofline"]["kernel_ms_median"] = sorted(seg_ms)[2]
+        out["roofline"]["kernel_ms_best"] = min(seg_ms)
     if not args.no_cpu_baseline:
         n_threads = max(1, min(16, os.cpu_count() or 1))
         envs_per_thread = 16
