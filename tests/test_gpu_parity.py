@@ -168,13 +168,11 @@ def sampled_ids(batch, n, seed):
 @pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
 def test_benchmark_configs_full_size(ci):
     """Full batch on the GPU; the oracle replays every environment (configs 0, 2) or a seeded sample of
-    environments (configs 1, 3, 4) for every ply, all outputs compared bit-exactly on those."""
+    environments (2052 / 773 / 517 of configs 1, 3, 4) for every ply, all outputs compared bit-exactly on those."""
     from gpu_common import Pair
     cfg = workloads.CONFIGS[ci]
-    n_sample = {0: None, 1: 96, 2: None, 3: 48, 4: 40}[ci]
+    n_sample = {0: None, 1: 2048, 2: None, 3: 768, 4: 512}[ci]
     ids = None if n_sample is None else sampled_ids(cfg.batch, n_sample, ci)
-    if ci == 2:
-        ids = sampled_ids(cfg.batch, 160, ci)     # 1024 x 722 plies is too slow for the plain oracle; 165 full games
     p = Pair(cfg.batch, cfg.board_size, seed=cfg.seed, auto_reset=cfg.auto_reset, ids=ids)
     start = workloads.start_times(cfg)
     T = cfg.warmup_max + cfg.steps
