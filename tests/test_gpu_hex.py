@@ -224,17 +224,17 @@ def whole_batch_properties(env, mask, obs):
 @pytest.mark.parametrize("k", [0, 1, 2])
 def test_full_size_configurations(k):
     """The three Hex workloads at full batch, in the launch shape bench.py times (fused sampler); the oracle replays
-    every environment (k = 0) or a seeded sample of them for every ply."""
+    every environment (1024 and 16384 games) or a seeded sample of ~8000 of the 262144 for every ply."""
     from paper_2303_17503_amd import workloads
     cfg = workloads.HEX_CONFIGS[k]
     rng = np.random.default_rng(100 + k)
     if k == 0:
         ids = None
     else:
-        n = 220 if k == 1 else 120
-        ids = np.unique(np.concatenate([[0, 1, 4, 5, cfg.batch - 1, cfg.batch - 2, cfg.batch - 5], rng.integers(0, cfg.batch, n)]))
+        n = 16384 if k == 1 else 8000
+        ids = None if n >= cfg.batch else np.unique(np.concatenate([[0, 1, 4, 5, cfg.batch - 1, cfg.batch - 2, cfg.batch - 5], rng.integers(0, cfg.batch, n)]))
     p = HexPair(cfg.batch, seed=cfg.seed, auto_reset=cfg.auto_reset, ids=ids)
-    plies = cfg.steps if k < 2 else 300
+    plies = cfg.steps if k < 2 else 400
     p.rollout(cfg.seed, 0, plies, fused=True, state_every=50)
     whole_batch_properties(p.env, p.mask, p.obs)
     assert p.n_compared == (cfg.batch if ids is None else len(ids)) * plies
