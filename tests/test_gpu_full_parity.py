@@ -1,0 +1,26 @@
+"""Every environment and every ply of every benchmark configuration, HIP path against CPU oracle, bit for bit
+(drawn actions, masks, observations, rewards, terminated flags every ply; exported state every 100 plies).
+The oracle side runs on 16 host threads; the two largest cases take ~40 s each."""
+import importlib.util
+import os
+
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+spec = importlib.util.spec_from_file_location("full_parity", os.path.join(HERE, "full_parity.py"))
+full_parity = importlib.util.module_from_spec(spec)
+spec.loader.exec_module(full_parity)
+
+EXPECTED = {("go", 0): 256 * 162, ("go", 1): 4096 * 1000, ("go", 2): 1024 * 722, ("go", 3): 16384 * 2000,
+            ("hex", 0): 1024 * 122, ("hex", 1): 16384 * 1000, ("hex", 2): 262144 * 500}
+
+
+@pytest.mark.parametrize("game,config", [("go", 0), ("go", 1), ("go", 2), ("go", 3), ("go", 4), ("hex", 0), ("hex", 1), ("hex", 2)])
+def test_every_environment_every_ply(game, config):
+    n = full_parity.run(full_parity.Args(game=game, config=config))
+    if (game, config) in EXPECTED:
+        assert n == EXPECTED[(game, config)]
+    else:
+        assert n > 65536 * 500          # configuration 4: 500 measured plies plus each game's own warm-up
