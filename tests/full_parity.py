@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 
 
 class Args:
-    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100):
+    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False):
         self.game, self.config, self.plies, self.threads, self.state_every = game, config, plies, threads, state_every
+        self.superko = superko
 
 
 def main():
@@ -35,9 +36,10 @@ def main():
     ap.add_argument("--plies", type=int, default=0, help="0 = warm-up + the configuration's measured plies")
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--state-every", type=int, default=100)
+    ap.add_argument("--superko", action="store_true", help="Go only: both sides with the positional-superko rule on")
     a = ap.parse_args()
     try:
-        run(Args(a.game, a.config, a.plies, a.threads, a.state_every))
+        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko))
     except AssertionError as e:
         print(e, flush=True)
         sys.exit(1)
@@ -63,6 +65,9 @@ def run(args):
     st_dev = None if start is None else torch.as_tensor(start, device="cuda")
 
     env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset) if go else pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
+    if args.superko:
+        assert go, "the superko rule is a Go option"
+        env.enable_superko()
     mask, obs = env.new_mask(), env.new_obs()
     rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
     term = torch.zeros(B, dtype=torch.uint8, device="cuda")
@@ -75,7 +80,7 @@ def run(args):
     def make(lo, hi):
         ids = np.arange(lo, hi, dtype=np.int32)
         if go:
-            return oracle.GoOracle(hi - lo, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids)
+            return oracle.GoOracle(hi - lo, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids, superko=args.superko)
         return hx.HexOracle(hi - lo, N, seed=seed, auto_reset=cfg.auto_reset, env_ids=ids)
 
     oracle.lib(); hx.lib()
@@ -127,7 +132,7 @@ def run(args):
         assert not bad, f"MISMATCH at ply {t}: {bad[0]}"
         if t % 100 == 99 or t == T - 1:
             print(f"[{time.time() - t0:6.0f} s] ply {t + 1}/{T}: all {B} environments agree", flush=True)
-    print(f"FULL PARITY OK: {cfg.name}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
+    print(f"FULL PARITY OK: {cfg.name}{' with superko' if args.superko else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
           f"reward and terminated flag compared; state every {args.state_every} plies; {len(shards)} oracle shards; {time.time() - t0:.0f} s", flush=True)
     pool.shutdown()
     return n_plies

@@ -24,3 +24,10 @@ def test_every_environment_every_ply(game, config):
         assert n == EXPECTED[(game, config)]
     else:
         assert n > 65536 * 500          # configuration 4: 500 measured plies plus each game's own warm-up
+
+
+@pytest.mark.parametrize("config", [1, 2, 3])
+def test_every_environment_every_ply_with_superko(config):
+    """The same with the positional-superko rule on (the oracle keeps every position of every game literally)."""
+    n = full_parity.run(full_parity.Args(game="go", config=config, superko=True))
+    assert n == EXPECTED[("go", config)]
