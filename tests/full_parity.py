@@ -24,9 +24,9 @@ sys.path.insert(0, ROOT)
 
 
 class Args:
-    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False):
+    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0):
         self.game, self.config, self.plies, self.threads, self.state_every = game, config, plies, threads, state_every
-        self.superko = superko
+        self.superko, self.rollout = superko, rollout
 
 
 def main():
@@ -37,9 +37,10 @@ def main():
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--state-every", type=int, default=100)
     ap.add_argument("--superko", action="store_true", help="Go only: both sides with the positional-superko rule on")
+    ap.add_argument("--rollout", type=int, default=0, help="L > 0: use the rollout kernel, L plies per launch, every ply recorded in its own slice")
     a = ap.parse_args()
     try:
-        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko))
+        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout))
     except AssertionError as e:
         print(e, flush=True)
         sys.exit(1)
@@ -116,23 +117,40 @@ def run(args):
         return None
 
     t0 = time.time()
-    acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
-    env.random_actions(seed, 0, st_dev, out=acts[0])
     n_plies = 0
-    for t in range(T):
-        h_act.copy_(acts[t & 1])
-        env.step_sample(acts[t & 1], seed, t + 1, st_dev, out=acts[(t + 1) & 1])
-        h_mask.copy_(mask); h_obs.copy_(obs); h_rew.copy_(rew); h_term.copy_(term)
-        g_state = None
-        if t % args.state_every == 0 or t == T - 1:
-            g_state = {k: v.cpu().numpy() for k, v in env.export_state().items()}
+
+    def compare(t, with_state):
+        nonlocal n_plies
+        g_state = {k: v.cpu().numpy() for k, v in env.export_state().items()} if with_state else None
         torch.cuda.synchronize()
         n_plies += int((n_act >= 0).sum())
         bad = [r for r in pool.map(lambda k: check(k, t, g_state), range(len(shards))) if r]
         assert not bad, f"MISMATCH at ply {t}: {bad[0]}"
         if t % 100 == 99 or t == T - 1:
             print(f"[{time.time() - t0:6.0f} s] ply {t + 1}/{T}: all {B} environments agree", flush=True)
-    print(f"FULL PARITY OK: {cfg.name}{' with superko' if args.superko else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
+
+    if args.rollout:
+        L = args.rollout
+        assert not args.superko, "the rollout kernel does not carry the superko tables"
+        tr = dict(actions=torch.empty((L, B), dtype=torch.int32, device="cuda"), rewards=torch.empty((L, B, 2), dtype=torch.float32, device="cuda"),
+                  terminated=torch.empty((L, B), dtype=torch.uint8, device="cuda"), mask=torch.empty((L,) + tuple(mask.shape), dtype=torch.uint8, device="cuda"),
+                  obs=torch.empty((L,) + tuple(obs.shape), dtype=torch.uint8, device="cuda"))
+        for t in range(0, T, L):
+            n = min(L, T - t)
+            env.rollout(n, seed, t, start_t=st_dev, slices=L, **tr)       # ply t+i of this launch lands in slice i
+            for i in range(n):
+                h_act.copy_(tr["actions"][i]); h_mask.copy_(tr["mask"][i]); h_obs.copy_(tr["obs"][i])
+                h_rew.copy_(tr["rewards"][i]); h_term.copy_(tr["terminated"][i])
+                compare(t + i, with_state=(i == n - 1))                     # the state on the device is the one after the launch
+    else:
+        acts = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(2)]
+        env.random_actions(seed, 0, st_dev, out=acts[0])
+        for t in range(T):
+            h_act.copy_(acts[t & 1])
+            env.step_sample(acts[t & 1], seed, t + 1, st_dev, out=acts[(t + 1) & 1])
+            h_mask.copy_(mask); h_obs.copy_(obs); h_rew.copy_(rew); h_term.copy_(term)
+            compare(t, with_state=(t % args.state_every == 0 or t == T - 1))
+    print(f"FULL PARITY OK: {cfg.name}{' with superko' if args.superko else ''}{' through the rollout kernel' if args.rollout else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
           f"reward and terminated flag compared; state every {args.state_every} plies; {len(shards)} oracle shards; {time.time() - t0:.0f} s", flush=True)
     pool.shutdown()
     return n_plies

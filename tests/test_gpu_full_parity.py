@@ -31,3 +31,10 @@ def test_every_environment_every_ply_with_superko(config):
     """The same with the positional-superko rule on (the oracle keeps every position of every game literally)."""
     n = full_parity.run(full_parity.Args(game="go", config=config, superko=True))
     assert n == EXPECTED[("go", config)]
+
+
+@pytest.mark.parametrize("game,config", [("go", 1), ("go", 3), ("hex", 1)])
+def test_every_environment_every_ply_through_the_rollout_kernel(game, config):
+    """The rollout kernel, 8 plies per launch with every ply recorded in its own slice."""
+    n = full_parity.run(full_parity.Args(game=game, config=config, rollout=8))
+    assert n == EXPECTED[(game, config)]
