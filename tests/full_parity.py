@@ -24,9 +24,9 @@ sys.path.insert(0, ROOT)
 
 
 class Args:
-    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0):
+    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0, seed=None):
         self.game, self.config, self.plies, self.threads, self.state_every = game, config, plies, threads, state_every
-        self.superko, self.rollout = superko, rollout
+        self.superko, self.rollout, self.seed = superko, rollout, seed
 
 
 def main():
@@ -38,9 +38,10 @@ def main():
     ap.add_argument("--state-every", type=int, default=100)
     ap.add_argument("--superko", action="store_true", help="Go only: both sides with the positional-superko rule on")
     ap.add_argument("--rollout", type=int, default=0, help="L > 0: use the rollout kernel, L plies per launch, every ply recorded in its own slice")
+    ap.add_argument("--seed", type=int, default=None, help="another seed than the configuration's (more trajectories of the same shape)")
     a = ap.parse_args()
     try:
-        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout))
+        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout, a.seed))
     except AssertionError as e:
         print(e, flush=True)
         sys.exit(1)
@@ -58,7 +59,8 @@ def run(args):
     assert torch.cuda.is_available(), "needs a GPU"
     go = args.game == "go"
     cfg = (workloads.CONFIGS if go else workloads.HEX_CONFIGS)[args.config]
-    B, N, seed = cfg.batch, cfg.board_size, cfg.seed
+    B, N = cfg.batch, cfg.board_size
+    seed = cfg.seed if args.seed is None else args.seed
     P = N * N
     planes = 17 if go else 4
     T = args.plies or (cfg.warmup_max + cfg.steps)
