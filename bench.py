@@ -248,6 +248,28 @@ def main():
                      "traffic": traffic, "kernel": kname, "kernel_ms": kern_ms, "algorithmic_bytes_per_ply": bytes_ply,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
     }
+    if args.mode == "fused" and not args.superko and K >= args.rollout_len:
+        # for information: the same workload through the rollout kernel (rollout_len plies per launch, state in registers)
+        Lr = args.rollout_len
+        Kr = K // Lr * Lr
+        env2 = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
+        bufs = dict(actions=torch.empty((1, B), dtype=torch.int32, device="cuda"), rewards=rew.view(1, B, 2), terminated=term.view(1, B),
+                    mask=mask.view(1, B, -1), obs=None if obs is None else obs.view(1, B, -1))
+        if pre + Wm:
+            env2.rollout(pre + Wm, seed, 0, start_t=start_dev, **bufs)
+        torch.cuda.synchronize()
+        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        tr0 = time.perf_counter()
+        r0.record()
+        for i in range(Kr // Lr):
+            env2.rollout(Lr, seed, pre + Wm + i * Lr, start_t=start_dev, **bufs)
+        r1.record()
+        torch.cuda.synchronize()
+        wall_r = time.perf_counter() - tr0
+        ms_r = r0.elapsed_time(r1) / Kr
+        out["rollout"] = {"value": B * Kr / wall_r, "unit": "env steps/s", "steps": Kr, "rollout_len": Lr, "kernel": "go_rollout_kernel<%d>" % N,
+                          "kernel_ms_per_ply": ms_r, "achieved": bytes_ply * B / (ms_r * 1e-3) / 1e9, "frac": bytes_ply * B / (ms_r * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "note": "pgxgo_rollout: the same plies and outputs with rollout_len plies per launch; not the headline value"}
     if args.mode == "fused" and seg_ms:
         out["roofline"]["kernel_ms_segments"] = seg_ms
         out["roofline"]["kernel_ms_median"] = sorted(seg_ms)[2]
