@@ -82,6 +82,16 @@ int pgxgo_reset(pgxgo_t h);
  * pgxgo_observe still work), rewards/terminated go to internal arrays read by the getters. */
 int pgxgo_bind_outputs(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev);
 
+/* Switches the buffers pgxgo_step writes to WITHOUT touching their contents (no emission, no copy): for callers
+ * that record a trajectory by stepping into a different slice every ply.  Same meanings and NULL handling as
+ * pgxgo_bind_outputs.  What the new buffers hold for an environment is undefined until a step call has written it
+ * (an environment stepped with action -1 writes nothing). */
+int pgxgo_set_output_buffers(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev);
+
+/* Fig. 2 legal_action_mask and observation of the current state in ONE launch (either pointer may be NULL, not both);
+ * the two getters pgxgo_legal_mask / pgxgo_observe below are this call with one buffer. */
+int pgxgo_emit(pgxgo_t h, uint8_t* mask_dev /* [batch][mask_pitch] */, uint8_t* obs_dev /* [batch][obs_pitch] */);
+
 /* Fig. 2 "step": applies actions_dev[batch] (int32) to all games: legality gate, stone placement,
  * chain merge, liberty count, capture, ko, history push, termination and area scoring,
  * optional auto-reset, then the next mover's legal mask and observation.  With auto-reset the
@@ -181,6 +191,13 @@ int32_t pgxgo_obs_bytes(int32_t board_size);            /* N*N*17 (Table 1: 9x9x
 
 const char* pgxgo_strerror(int code);
 int pgxgo_last_hip_error(void); /* hipError_t of the most recent PGXGO_EHIP on this thread, else 0 */
+
+/* Measurement helpers for the benchmark (no game logic).  pgxgo_fill_probe: one launch that fills nbytes (a multiple
+ * of 16, dst_dev 16-byte aligned) with 16-byte vector stores of `value` -- the plain-store ceiling the step kernel's
+ * output rate is compared with.  pgxgo_empty_probe: `count` back-to-back launches of an empty kernel, enqueued from
+ * one host loop (the time per launch is the gap between dependent launches on one stream). */
+int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, void* stream);
+int pgxgo_empty_probe(void* stream, int32_t count);
 
 /* Harness helper: cross-lane shift semantics of the target (lane i reads lane i-1 / i+1, zero at
  * the wavefront ends).  Writes out_dev[0..63] = value seen from below, out_dev[64..127] = value

@@ -69,6 +69,11 @@ int pgxhex_reset(pgxhex_t h);
 int pgxhex_bind_outputs(pgxhex_t h, uint8_t* mask_dev /* [batch][122] */, uint8_t* obs_dev /* [batch][484] */,
                         float* rewards_dev /* [batch][2] by player id */, uint8_t* terminated_dev /* [batch] */);
 
+/* Switches the buffers the step calls write to WITHOUT touching their contents (no emission, no copy): for callers
+ * that record a trajectory by stepping into a different slice every ply.  NULL handling as in pgxhex_bind_outputs.
+ * What the new buffers hold for a game is undefined until a step call has written it (action -1 writes nothing). */
+int pgxhex_set_output_buffers(pgxhex_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev);
+
 /* Fig. 2 "step": applies actions_dev[batch] (int32) to every game: legality gate, placement or swap, winner test
  * (Appendix C "Hex", Rules), rewards +1/-1 (Reward), auto-reset, next legal mask and observation. */
 int pgxhex_step(pgxhex_t h, const int32_t* actions_dev);

@@ -34,6 +34,10 @@ def lib():
         L.pgxgo_destroy.argtypes = [vp]
         L.pgxgo_reset.argtypes = [vp]
         L.pgxgo_bind_outputs.argtypes = [vp, vp, vp, vp, vp]
+        L.pgxgo_set_output_buffers.argtypes = [vp, vp, vp, vp, vp]
+        L.pgxgo_emit.argtypes = [vp, vp, vp]
+        L.pgxgo_fill_probe.argtypes = [vp, C.c_size_t, u32, vp]
+        L.pgxgo_empty_probe.argtypes = [vp, i32]
         L.pgxgo_step.argtypes = [vp, vp]
         L.pgxgo_random_actions.argtypes = [vp, u32, u32, vp, vp]
         L.pgxgo_step_sample.argtypes = [vp, vp, u32, u32, vp, vp]
@@ -127,6 +131,21 @@ class GoEnv:
         if terminated is not None: _need(terminated, torch.uint8, (self.B,), "terminated")
         _check(lib().pgxgo_bind_outputs(self._h, _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)), "pgxgo_bind_outputs")
         self.mask_out, self.obs_out, self.rewards_out, self.terminated_out = mask, obs, rewards, terminated
+
+    def set_output_buffers(self, mask=None, obs=None, rewards=None, terminated=None):
+        """Switch the buffers step() writes to without emitting or copying anything (trajectory recording)."""
+        if mask is not None: _need(mask, torch.uint8, (self.B, self.mask_pitch), "mask")
+        if obs is not None: _need(obs, torch.uint8, (self.B, self.obs_pitch), "obs")
+        if rewards is not None: _need(rewards, torch.float32, (self.B, 2), "rewards")
+        if terminated is not None: _need(terminated, torch.uint8, (self.B,), "terminated")
+        _check(lib().pgxgo_set_output_buffers(self._h, _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)), "pgxgo_set_output_buffers")
+        self.mask_out, self.obs_out, self.rewards_out, self.terminated_out = mask, obs, rewards, terminated
+
+    def emit(self, mask=None, obs=None):
+        """Legal mask and observation of the current state in one launch."""
+        if mask is not None: _need(mask, torch.uint8, (self.B, self.mask_pitch), "mask")
+        if obs is not None: _need(obs, torch.uint8, (self.B, self.obs_pitch), "obs")
+        _check(lib().pgxgo_emit(self._h, _ptr(mask), _ptr(obs)), "pgxgo_emit")
 
     # ---- the environment API ------------------------------------------------------------------------------
     def reset(self):
@@ -246,6 +265,17 @@ class GoEnv:
         for n, dt in self.STATE_FIELDS[:-1]:
             args.append(_ptr(_need(st[n], dt, self._state_shape(n), n)))
         _check(lib().pgxgo_import_state(self._h, *args), "pgxgo_import_state")
+
+
+def fill_probe(dst, value=0):
+    """One plain fill of the uint8 cuda tensor `dst` (16-byte aligned, size a multiple of 16) with 16-byte stores."""
+    _check(lib().pgxgo_fill_probe(_ptr(dst), dst.numel() * dst.element_size(), value & 0xFFFFFFFF,
+                                  C.c_void_p(torch.cuda.current_stream().cuda_stream)), "pgxgo_fill_probe")
+
+
+def empty_probe(count=1):
+    """`count` back-to-back launches of an empty kernel on the current stream, enqueued by one C loop."""
+    _check(lib().pgxgo_empty_probe(C.c_void_p(torch.cuda.current_stream().cuda_stream), int(count)), "pgxgo_empty_probe")
 
 
 def lane_shift_probe(values):

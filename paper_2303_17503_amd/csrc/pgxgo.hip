@@ -1214,6 +1214,14 @@ __global__ void lane_shift_probe_kernel(const uint32_t* in, uint32_t* out) {
   out[64 + threadIdx.x] = from_lane_above(x);
 }
 
+// Measurement helpers: a plain fill with 16-byte stores (the practical write ceiling of the machine on the same
+// buffers the step kernel writes) and an empty kernel (the gap between dependent launches on one stream).
+__global__ void __launch_bounds__(256) fill_probe_kernel(uint4* __restrict__ dst, size_t n16, uint32_t value) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte store per thread
+  if (i < n16) dst[i] = make_uint4(value, value, value, value);
+}
+__global__ void empty_probe_kernel() {}
+
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 template <int N>
@@ -1479,6 +1487,19 @@ int pgxgo_bind_outputs(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* re
   return PGXGO_OK;
 }
 
+int pgxgo_set_output_buffers(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
+  if (!h) return PGXGO_EINVAL;
+  h->mask_out = mask_dev; h->obs_out = obs_dev;
+  h->rew_out = rewards_dev ? rewards_dev : h->rew_int;
+  h->term_out = terminated_dev ? terminated_dev : h->term_int;
+  return PGXGO_OK;
+}
+
+int pgxgo_emit(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev) {
+  if (!h || (!mask_dev && !obs_dev)) return PGXGO_EINVAL;
+  return DISPATCH_N(h, launch_emit<19>(h, mask_dev, obs_dev), launch_emit<9>(h, mask_dev, obs_dev));
+}
+
 int pgxgo_step(pgxgo_t h, const int32_t* actions_dev) {
   if (!h || !actions_dev) return PGXGO_EINVAL;
   return DISPATCH_N(h, launch_step<19>(h, actions_dev, false, 0u, 0u, nullptr, nullptr), launch_step<9>(h, actions_dev, false, 0u, 0u, nullptr, nullptr));
@@ -1626,6 +1647,23 @@ const char* pgxgo_strerror(int code) {
 }
 
 int pgxgo_last_hip_error(void) { return g_last_hip; }
+
+int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, void* stream) {
+  if (!dst_dev || ((uintptr_t)dst_dev & 15u) != 0 || (nbytes & 15u) != 0) return PGXGO_EINVAL;
+  if (nbytes == 0) return PGXGO_OK;
+  const size_t n16 = nbytes / 16;
+  if ((n16 + 255) / 256 > 0x7FFFFFFFull) return PGXGO_EINVAL;
+  hipLaunchKernelGGL(fill_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (uint4*)dst_dev, n16, value);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
+
+int pgxgo_empty_probe(void* stream, int32_t count) {
+  if (count < 0) return PGXGO_EINVAL;
+  for (int32_t i = 0; i < count; ++i) hipLaunchKernelGGL(empty_probe_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream);
+  HIPCHK(hipGetLastError());
+  return PGXGO_OK;
+}
 
 int pgxgo_lane_shift_probe(const uint32_t* in_dev, uint32_t* out_dev, void* stream) {
   if (!in_dev || !out_dev) return PGXGO_EINVAL;

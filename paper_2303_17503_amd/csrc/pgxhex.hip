@@ -301,7 +301,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   emit_outputs(L, bk, wt, m, wave, a.B, a.mask, a.obs, lds_mask[wib], lds_obs[wib], lut);
 
   if (SAMPLE) {
-    const bool wait = a.start_t && L.boardok && a.sample_t < (uint32_t)a.start_t[L.b];
+    const bool wait = a.start_t && L.boardok && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
     const int next = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.sample_seed, a.sample_t, wait);
     if (L.valid && L.r == 0) a.next_actions[L.b] = next;
   }
@@ -381,7 +381,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_random_actions_kernel
   const Lane L(wave, lane, B);
   const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
   const Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0u, 0u, 0u, 0u));
-  const bool wait = start_t && L.boardok && t < (uint32_t)start_t[L.b];
+  const bool wait = start_t && L.boardok && (int64_t)t < (int64_t)start_t[L.b];
   const int next = draw_action(L, L.full & ~((word & 0xFFFFu) | (word >> 16)), m.steps == 1, seed, t, wait);
   if (L.valid && L.r == 0) actions[L.b] = next;
 }
@@ -571,6 +571,14 @@ int pgxhex_bind_outputs(pgxhex_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* 
   h->rew_out = new_rew; h->term_out = new_term;
   h->mask_out = mask_dev; h->obs_out = obs_dev;
   if (mask_dev || obs_dev) return launch_emit(h, mask_dev, obs_dev);
+  return PGXHEX_OK;
+}
+
+int pgxhex_set_output_buffers(pgxhex_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
+  if (!h) return PGXHEX_EINVAL;
+  h->mask_out = mask_dev; h->obs_out = obs_dev;
+  h->rew_out = rewards_dev ? rewards_dev : h->rew_int;
+  h->term_out = terminated_dev ? terminated_dev : h->term_int;
   return PGXHEX_OK;
 }
 

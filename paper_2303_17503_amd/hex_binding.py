@@ -25,6 +25,7 @@ def lib():
         L.pgxhex_destroy.argtypes = [vp]
         L.pgxhex_reset.argtypes = [vp]
         L.pgxhex_bind_outputs.argtypes = [vp, vp, vp, vp, vp]
+        L.pgxhex_set_output_buffers.argtypes = [vp, vp, vp, vp, vp]
         L.pgxhex_step.argtypes = [vp, vp]
         L.pgxhex_random_actions.argtypes = [vp, u32, u32, vp, vp]
         L.pgxhex_step_sample.argtypes = [vp, vp, u32, u32, vp, vp]
@@ -87,6 +88,15 @@ class HexEnv:
         if rewards is not None: _need(rewards, torch.float32, (self.B, 2), "rewards")
         if terminated is not None: _need(terminated, torch.uint8, (self.B,), "terminated")
         _check(lib().pgxhex_bind_outputs(self._h, _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)), "pgxhex_bind_outputs")
+        self.mask_out, self.obs_out, self.rewards_out, self.terminated_out = mask, obs, rewards, terminated
+
+    def set_output_buffers(self, mask=None, obs=None, rewards=None, terminated=None):
+        """Switch the buffers the step calls write to without emitting or copying anything (trajectory recording)."""
+        if mask is not None: _need(mask, torch.uint8, (self.B, A), "mask")
+        if obs is not None: _need(obs, torch.uint8, (self.B, OBS), "obs")
+        if rewards is not None: _need(rewards, torch.float32, (self.B, 2), "rewards")
+        if terminated is not None: _need(terminated, torch.uint8, (self.B,), "terminated")
+        _check(lib().pgxhex_set_output_buffers(self._h, _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)), "pgxhex_set_output_buffers")
         self.mask_out, self.obs_out, self.rewards_out, self.terminated_out = mask, obs, rewards, terminated
 
     def reset(self):

@@ -54,7 +54,7 @@ def run(args):
     import oracle
     import paper_2303_17503_amd as pg
     from oracle import hex as hx
-    from paper_2303_17503_amd import workloads
+    import workloads
 
     assert torch.cuda.is_available(), "needs a GPU"
     go = args.game == "go"

@@ -15,7 +15,7 @@ sys.path.insert(0, ROOT)
 
 import oracle  # noqa: E402
 from oracle import hex as hex_oracle  # noqa: E402
-from paper_2303_17503_amd import workloads  # noqa: E402  (configuration table only)
+import workloads  # noqa: E402  (configuration table only; a top-level module outside the product package)
 
 ENVS = 8
 

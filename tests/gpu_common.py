@@ -64,7 +64,7 @@ class Pair:
         if obs:
             assert (self.gpu_obs() == o.observe()).all(), f"obs {tag}"
         r_g, r_c = self.gpu_rew(), o.rewards()
-        assert r_g.tobytes() == r_c.tobytes() or (r_g == r_c).all(), f"rewards {tag}"
+        assert r_g.tobytes() == r_c.tobytes(), f"rewards {tag}"   # exact bytes: -0.0 must not pass for 0.0
         assert (self.gpu_term() == o.terminated()).all(), f"terminated {tag}"
         assert (self.pick(self.env.current_player()) == o.current_player()).all(), f"current_player {tag}"
         if state:

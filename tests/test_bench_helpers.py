@@ -1,6 +1,6 @@
 """CPU checks of the benchmark's byte model and of the workload table."""
 import bench
-from paper_2303_17503_amd import workloads
+import workloads
 
 
 def test_algorithmic_bytes_per_ply():

@@ -6,7 +6,7 @@ import os
 import numpy as np
 import pytest
 
-from paper_2303_17503_amd import workloads
+import workloads
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 spec = importlib.util.spec_from_file_location("make_digests", os.path.join(HERE, "golden", "make_digests.py"))

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import positions as pos
-from paper_2303_17503_amd import workloads
+import workloads
 
 pytestmark = pytest.mark.gpu
 
@@ -402,6 +402,42 @@ def test_slot_step_and_copy_for_tree_search(N, pool, auto_reset):
                    torch.as_tensor(np.array([3, 4], np.int32), device="cuda"), terminated=term)
     assert to_np(term)[1] == 255
     check_pool("bad slot ignored")
+
+
+@pytest.mark.parametrize("N,B", [(19, 100), (9, 500)])
+def test_switching_output_buffers_and_the_combined_getter(N, B):
+    """pgxgo_set_output_buffers: a different slice every ply records the trajectory, no emission or copy at the switch;
+    pgxgo_emit: mask and observation of the current state in one launch."""
+    from gpu_common import Pair, to_np
+    seed, S = 21, 5
+    p = Pair(B, N, seed=seed, auto_reset=True)
+    masks = [torch.full_like(p.mask, 7) for _ in range(S)]
+    obss = [torch.full_like(p.obs, 7) for _ in range(S)]
+    rews = [torch.full_like(p.rew, 7.0) for _ in range(S)]
+    terms = [torch.full_like(p.term, 7) for _ in range(S)]
+    p.env.set_output_buffers(masks[0], obss[0], rews[0], terms[0])
+    assert (to_np(masks[0]) == 7).all() and (to_np(rews[0]) == 7).all()          # nothing was written at the switch
+    a = p.env.random_actions(seed, 0)
+    for t in range(40):
+        i = t % S
+        p.env.set_output_buffers(masks[i], obss[i], rews[i], terms[i])
+        a_c = p.orc.random_actions(seed, t)
+        assert (to_np(a) == a_c).all()
+        a = p.env.step_sample(a, seed, t + 1)
+        p.orc.step(a_c)
+        assert (to_np(masks[i]) == p.orc.legal_mask()).all() and (to_np(obss[i]).reshape(B, N, N, 17) == p.orc.observe()).all(), t
+        assert to_np(rews[i]).tobytes() == p.orc.rewards().tobytes() and (to_np(terms[i]) == p.orc.terminated()).all(), t
+    m2, o2 = torch.full_like(p.mask, 9), torch.full_like(p.obs, 9)
+    p.env.emit(m2, o2)
+    assert (to_np(m2) == p.orc.legal_mask()).all() and (to_np(o2).reshape(B, N, N, 17) == p.orc.observe()).all()
+    m3 = torch.full_like(p.mask, 9)
+    p.env.emit(mask=m3)
+    assert (to_np(m3) == p.orc.legal_mask()).all()
+    p.env.set_output_buffers()                                                   # back to the internal rewards / terminated arrays
+    a_c = p.orc.random_actions(seed, 40)
+    p.env.step(torch.as_tensor(a_c, device="cuda")); p.orc.step(a_c)
+    assert to_np(p.env.rewards()).tobytes() == p.orc.rewards().tobytes() and (to_np(p.env.terminated()) == p.orc.terminated()).all()
+    assert (to_np(p.env.legal_mask()) == p.orc.legal_mask()).all()
 
 
 @pytest.mark.parametrize("N,wb", [(19, 1), (19, 2), (19, 3), (9, 1), (9, 2), (9, 3), (9, 4), (9, 5), (9, 6)])

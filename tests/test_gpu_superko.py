@@ -145,7 +145,7 @@ def test_other_entry_points_refuse_while_the_rule_is_on():
 
 def test_headline_shape_with_the_rule_on():
     """19x19 x 16384 in the launch shape bench.py times, a seeded sample of environments replayed by the oracle."""
-    from paper_2303_17503_amd import workloads
+    import workloads
     cfg = workloads.CONFIGS[3]
     rng = np.random.default_rng(77)
     ids = np.unique(np.concatenate([[0, 1, 2, cfg.batch - 1, cfg.batch - 2], rng.integers(0, cfg.batch, 40)]))

@@ -7,7 +7,7 @@ import numpy as np
 
 import oracle
 import paper_2303_17503_amd as pg
-from paper_2303_17503_amd import workloads
+import workloads
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 

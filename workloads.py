@@ -24,21 +24,22 @@ class Config:
     emit_obs: bool = True
     komi_x2: int = 15
     game: str = "go"
+    preroll: int = 0      # benchmark only: untimed plies played before the timed window, so that it lies in the workload's steady regime
 
 
 CONFIGS = [
-    Config("go9_b256_fullgame", 9, 256, 0, False, 162),
-    Config("go9_b4096_autoreset", 9, 4096, 1, True, 1000),
-    Config("go19_b1024_fullgame", 19, 1024, 2, False, 722),
-    Config("go19_b16384_autoreset_obs", 19, 16384, 3, True, 2000),
-    Config("go19_b65536_midgame", 19, 65536, 4, True, 500, warmup_max=300),
+    Config("go9_b256_fullgame", 9, 256, 0, False, 162, preroll=30),
+    Config("go9_b4096_autoreset", 9, 4096, 1, True, 1000, preroll=300),
+    Config("go19_b1024_fullgame", 19, 1024, 2, False, 722, preroll=200),
+    Config("go19_b16384_autoreset_obs", 19, 16384, 3, True, 2000, preroll=600),
+    Config("go19_b65536_midgame", 19, 65536, 4, True, 500, warmup_max=300),   # its warm-up is its pre-roll
 ]
 
 # Hex 11x11 (the second workload): random legal play from the empty board as in Sec. 4.1; a game lasts at most 122 plies
 HEX_CONFIGS = [
-    Config("hex11_b1024_fullgame", 11, 1024, 5, False, 122, game="hex"),
-    Config("hex11_b16384_autoreset", 11, 16384, 6, True, 1000, game="hex"),
-    Config("hex11_b262144_autoreset", 11, 262144, 7, True, 500, game="hex"),
+    Config("hex11_b1024_fullgame", 11, 1024, 5, False, 122, game="hex", preroll=15),
+    Config("hex11_b16384_autoreset", 11, 16384, 6, True, 1000, game="hex", preroll=200),
+    Config("hex11_b262144_autoreset", 11, 262144, 7, True, 500, game="hex", preroll=200),
 ]
 
 _M = np.uint64(0xFFFFFFFF)
