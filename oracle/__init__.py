@@ -37,6 +37,8 @@ def lib():
         L.oracle_area.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.oracle_chain.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.oracle_set_superko.argtypes = [C.c_void_p, C.c_int]
+        L.oracle_repeats_literal.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        L.oracle_seen_count.argtypes = [C.c_void_p, C.c_int]
         _lib = L
     return _lib
 
@@ -47,6 +49,16 @@ def _p(a):
 
 def hash4(seed, tag, env, t):
     return int(lib().oracle_hash(seed & 0xFFFFFFFF, tag & 0xFFFFFFFF, env & 0xFFFFFFFF, t & 0xFFFFFFFF))
+
+
+def superko_mode(mode):
+    """False / 0 -> 0 (off), True / 1 -> 1 (at play time), "mask" / 2 -> 2 (honoured by the legal mask)."""
+    if mode == "mask":
+        return 2
+    m = int(mode)
+    if m not in (0, 1, 2):
+        raise ValueError("superko mode must be 0, 1, 2 or 'mask'")
+    return m
 
 
 class State:
@@ -82,11 +94,20 @@ class GoOracle:
         if not self._h:
             raise ValueError("oracle_create rejected its arguments")
         if superko:
-            self.set_superko(True)
+            self.set_superko(superko)
 
-    def set_superko(self, on):
-        """Positional superko: a play that recreates an earlier position of the game is an illegal action."""
-        lib().oracle_set_superko(self._h, int(bool(on)))
+    def set_superko(self, mode):
+        """Positional superko.  False / 0: off.  "mask" / 2: the rule proper, the legal mask leaves out every play that
+        would recreate an earlier position of the game.  True / 1: looked at only when the move is played (the
+        offender loses), the mask keeps showing the simple-ko set."""
+        lib().oracle_set_superko(self._h, superko_mode(mode))
+
+    def repeats_literal(self, b, p):
+        """Would the mover's play on empty point p recreate an earlier position of environment b (literal comparison)?"""
+        return bool(lib().oracle_repeats_literal(self._h, int(b), int(p)))
+
+    def seen_count(self, b):
+        return int(lib().oracle_seen_count(self._h, int(b)))
 
     def __del__(self):
         h, self._h = getattr(self, "_h", None), None

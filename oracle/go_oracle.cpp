@@ -7,8 +7,9 @@
 // komi added to White's score, 2x8 history planes + one colour plane, the last
 // action is pass, rewards +1/-1/0).  Where the paper is silent (simple ko,
 // suicide illegal, ply cap 2*N*N, illegal action ends the game, counter-based
-// action sampler, positional superko as an option) each reading is stated next to
-// the code that implements it.
+// action sampler, positional superko as an option in two readings: honoured by the
+// legal mask, or enforced only when the move is played) each reading is stated next
+// to the code that implements it.
 //
 // Only tests, the smoke check and the CPU-baseline leg of the benchmark may use
 // this file.  It shares no code, header, table or helper with the HIP library.
@@ -49,15 +50,20 @@ struct Env {
   uint32_t episode;           // number of resets so far
   uint32_t env_id;            // global environment index used by the hashes
   // positional superko (option): every whole-board position this episode has shown so far, the empty
-  // starting board included, kept literally
+  // starting board included, kept literally (with its two stone counts next to it)
   std::vector<std::array<int8_t, kMaxP>> seen;
+  std::vector<std::array<int, 2>> seen_counts;   // {black stones, white stones} of seen[i]
 };
 
 struct Oracle {
   int B, N, P;
   uint32_t seed;
   int komi_x2, max_steps, auto_reset;
-  int superko = 0;                // 1: a play that recreates an earlier position of the game is an illegal action
+  // Positional superko (Tromp-Taylor: a play may not recreate an earlier whole-board position of the game).
+  // 0: off (simple ko only).  2: the rule proper -- the legal mask leaves such plays out, so playing one is an
+  // illegal action like any other.  1: the rule is looked at only when the move is played (the offender loses),
+  // while the legal mask keeps showing the simple-ko set.
+  int superko = 0;
   std::vector<Env> env;
   std::vector<float> out_rew;     // [B][2], by player id: values of the last step call
   std::vector<uint8_t> out_term;  // [B]
@@ -206,24 +212,41 @@ void area_score(const int8_t* board, int N, int* area_black, int* area_white) {
 }
 
 // ---- positional superko (Appendix C "Go": Tromp-Taylor rules; their repetition rule forbids a play that
-// recreates any earlier whole-board position of the game).  Reading: enforced when the move is played (the
-// offender loses like for any illegal action); the legal mask keeps showing the simple-ko set.
+// recreates any earlier whole-board position of the game).
+void stone_counts(const int8_t* board, int* nb, int* nw) {
+  int b = 0, w = 0;
+  for (int p = 0; p < kMaxP; ++p) { if (board[p] == 1) ++b; else if (board[p] == -1) ++w; }
+  *nb = b; *nw = w;
+}
 void remember(Env& e) {
   std::array<int8_t, kMaxP> pos;
   std::memcpy(pos.data(), e.board, kMaxP);
   e.seen.push_back(pos);
+  int nb, nw;
+  stone_counts(e.board, &nb, &nw);
+  e.seen_counts.push_back({nb, nw});
 }
+// the literal test: compare the whole board with every earlier position
 bool seen_before(const Env& e, const int8_t* board) {
   for (const auto& pos : e.seen)
     if (std::memcmp(pos.data(), board, kMaxP) == 0) return true;
   return false;
 }
+// The same test, skipping the earlier positions whose stone counts differ from the board's (equal boards have
+// equal counts); used where every legal point of every ply is tried.  Pinned against seen_before by the tests.
+bool seen_before_counted(const Env& e, const int8_t* board) {
+  int nb, nw;
+  stone_counts(board, &nb, &nw);
+  for (size_t i = 0; i < e.seen.size(); ++i)
+    if (e.seen_counts[i][0] == nb && e.seen_counts[i][1] == nw && std::memcmp(e.seen[i].data(), board, kMaxP) == 0) return true;
+  return false;
+}
 // would playing `col` on p (a move the simple rules allow) recreate an earlier position?
-bool repeats_position(const Env& e, int N, int p, int col) {
+bool repeats_position(const Env& e, int N, int p, int col, bool literal) {
   int8_t tmp[kMaxP];
   std::memcpy(tmp, e.board, kMaxP);
   place_and_capture(tmp, N, p, col, nullptr);
-  return seen_before(e, tmp);
+  return literal ? seen_before(e, tmp) : seen_before_counted(e, tmp);
 }
 
 void env_reset(Oracle* o, Env& e) {
@@ -232,7 +255,7 @@ void env_reset(Oracle* o, Env& e) {
   e.to_play = 1; e.ko = -1; e.steps = 0; e.passes = 0; e.terminated = 0;
   // Fig. 2: which player acts first is drawn by a PRNG, independently of colour.
   e.black_player = (int)(hash4(o->seed, 1u, e.env_id, e.episode) & 1u);
-  e.seen.clear();
+  e.seen.clear(); e.seen_counts.clear();
   if (o->superko) remember(e);
 }
 
@@ -241,6 +264,9 @@ void env_outputs(Oracle* o, int b) {
   const int P = o->P;
   uint8_t* m = &o->mask[(size_t)b * (P + 1)];
   legal_by_chains(e.board, o->N, e.to_play, e.ko, m);
+  if (o->superko == 2)   // the rule proper: try every point the simple rules allow; pass never repeats by a play
+    for (int p = 0; p < P; ++p)
+      if (m[p] && repeats_position(e, o->N, p, e.to_play, false)) m[p] = 0;
   // Observation of the player to move (Appendix C "Go", Observation): for each of
   // the last 8 positions, most recent first, one plane of the mover's stones and
   // one of the opponent's; the 17th plane is all ones when black is to move.
@@ -269,7 +295,7 @@ void env_step(Oracle* o, int b, int a) {
   const int mover = (col == 1) ? e.black_player : 1 - e.black_player;
   const uint8_t* m = &o->mask[(size_t)b * (P + 1)];
   bool ended = false;
-  if (a < 0 || a > P || !m[a] || (o->superko && a < P && repeats_position(e, N, a, col))) {
+  if (a < 0 || a > P || !m[a] || (o->superko == 1 && a < P && repeats_position(e, N, a, col, true))) {
     // Illegal action: the game ends at once, the offender loses; the position,
     // ply counter and side to move stay as they were.
     o->illegal[b] += 1;
@@ -320,13 +346,16 @@ void env_step(Oracle* o, int b, int a) {
 }
 
 void rebuild_seen(Oracle* o, Env& e) {
-  e.seen.clear();
+  e.seen.clear(); e.seen_counts.clear();
   if (!o->superko) return;
   for (int i = kHist - 1; i >= 0; --i) {
     std::array<int8_t, kMaxP> pos;
     pos.fill(0);
     std::memcpy(pos.data(), e.hist[i], o->P);
     e.seen.push_back(pos);
+    int nb, nw;
+    stone_counts(pos.data(), &nb, &nw);
+    e.seen_counts.push_back({nb, nw});
   }
   remember(e);
 }
@@ -447,11 +476,21 @@ void oracle_import_state(void* h, const int8_t* board, const int8_t* history, co
 
 // Switches positional superko on or off.  The positions known from then on are the ones the state still
 // carries: the 8 history positions (entries from before the game started are the empty board) and the current one.
-void oracle_set_superko(void* h, int on) {
+// mode 0: off; 1: looked at only when the move is played; 2: honoured by the legal mask (the rule proper).
+void oracle_set_superko(void* h, int mode) {
   Oracle* o = (Oracle*)h;
-  o->superko = on ? 1 : 0;
-  for (int b = 0; b < o->B; ++b) rebuild_seen(o, o->env[b]);
+  o->superko = (mode == 1 || mode == 2) ? mode : 0;
+  for (int b = 0; b < o->B; ++b) { rebuild_seen(o, o->env[b]); env_outputs(o, b); }
 }
+
+// For the pins: would playing the mover's colour on p recreate an earlier position of environment b, by the literal
+// whole-board comparison with every earlier position (no count shortcut)?  p must be empty.
+int oracle_repeats_literal(void* h, int b, int p) {
+  Oracle* o = (Oracle*)h;
+  const Env& e = o->env[b];
+  return repeats_position(e, o->N, p, e.to_play, true) ? 1 : 0;
+}
+int oracle_seen_count(void* h, int b) { return (int)((Oracle*)h)->env[b].seen.size(); }
 
 // ---- stand-alone rule functions on a caller-supplied board (used by the pins) ----
 void oracle_legal_trial(const int8_t* board, int N, int to_play, int ko, uint8_t* mask /*[P+1]*/) {

@@ -1,5 +1,7 @@
-"""Pins of the oracle's positional superko option (Appendix C "Go": Tromp-Taylor rules): a hand-built
-send-two-return-one cycle, a triple ko, and the independent Python implementation on small boards.  No GPU."""
+"""Pins of the oracle's positional superko option (Appendix C "Go": Tromp-Taylor rules) in both readings -- the rule
+proper, honoured by the legal mask ("mask"), and the one enforced only when the move is played (True): a hand-built
+send-two-return-one cycle, hand-built histories with a repeating play that captures nothing / something, the
+independent Python implementation on small boards, and the literal whole-board comparison.  No GPU."""
 import itertools
 
 import numpy as np
@@ -148,3 +150,148 @@ def test_import_keeps_the_history_window():
     q2.set_superko(True)                                                   # switching on later rebuilds the set from the window as well
     q2.step([RETURN_ONE])
     assert q2.terminated()[0] == 1
+
+
+# ---- the rule proper: the legal mask leaves out every play that would recreate an earlier position -------------------
+
+def test_mask_leaves_out_the_returning_stone():
+    o = oracle.GoOracle(1, N9, superko="mask")
+    play(o, SEND_TWO)
+    m = o.legal_mask()[0]
+    assert m[RETURN_ONE] == 0 and m[PASS] == 1
+    simple = oracle.legal_chains(o.export_state().board[0], N9, 1, -1)
+    assert simple[RETURN_ONE] == 1 and (m == simple).sum() == N9 * N9          # the only point the rule takes away
+    mover = o.current_player()[0]
+    before = o.export_state().board.copy()
+    o.step([RETURN_ONE])                                                       # played anyway: an illegal action like any other
+    assert o.terminated()[0] == 1 and o.illegal_count()[0] == 1 and o.rewards()[0, mover] == -1
+    assert (o.export_state().board == before).all()
+    q = oracle.GoOracle(1, N9, superko="mask")
+    play(q, SEND_TWO)
+    q.step([a9(5, 5)]); q.step([PASS])
+    assert q.legal_mask()[0, RETURN_ONE] == 1                                  # another stone stands elsewhere now: no repeat
+
+
+def hand_history(cur, earlier, to_play):
+    """State whose current board is `cur` and whose previous position (one ply ago) is `earlier` (dicts point -> colour)."""
+    s = oracle.State(1, N9 * N9)
+    for p, v in cur.items():
+        s.board[0, p] = v
+    s.history[0, 0] = s.board[0]
+    for p, v in earlier.items():
+        s.history[0, 1, p] = v
+    s.ko[0] = -1; s.to_play[0] = to_play; s.steps[0] = 20
+    return s
+
+
+def test_repeating_play_that_captures_nothing():
+    # the earlier position is the current one plus a black stone on (4,4): Black's play there would bring it back
+    cur = {a9(2, 2): 1, a9(6, 6): -1, a9(3, 7): -1}
+    earlier = dict(cur); earlier[a9(4, 4)] = 1
+    for mode, expect in ((0, 1), (1, 1), ("mask", 0)):
+        o = oracle.GoOracle(1, N9, superko=mode)
+        o.import_state(hand_history(cur, earlier, 1))
+        m = o.legal_mask()[0]
+        assert m[a9(4, 4)] == expect and m[a9(4, 5)] == 1
+        o.step([a9(4, 4)])
+        assert o.terminated()[0] == (0 if mode == 0 else 1)
+    w = oracle.GoOracle(1, N9, superko="mask")                                  # White's stone on the same point gives another position
+    w.import_state(hand_history(cur, earlier, -1))
+    assert w.legal_mask()[0, a9(4, 4)] == 1
+
+
+def test_repeating_play_that_captures():
+    # White stones (0,0),(0,1) have one liberty left at (0,2) next to black (1,0),(1,1); Black takes them there.
+    # An earlier position equal to the result makes that capture a repetition; a different capture size or stone does not.
+    cur = {a9(0, 0): -1, a9(0, 1): -1, a9(1, 0): 1, a9(1, 1): 1, a9(7, 7): -1}
+    after = {a9(1, 0): 1, a9(1, 1): 1, a9(7, 7): -1, a9(0, 2): 1}
+    o = oracle.GoOracle(1, N9, superko="mask")
+    o.import_state(hand_history(cur, after, 1))
+    assert o.legal_mask()[0, a9(0, 2)] == 0
+    near = dict(after); near[a9(0, 1)] = -1                                    # only one of the two stones gone: not what the capture gives
+    o.import_state(hand_history(cur, near, 1))
+    assert o.legal_mask()[0, a9(0, 2)] == 1
+
+
+@pytest.mark.parametrize("N,depth", [(2, 7), (3, 4)])
+def test_mask_level_exhaustive_against_python(N, depth):
+    A = N * N + 1
+    taken = 0
+    for seq in itertools.product(range(A), repeat=depth):
+        ref = RefGame(N, superko=True)
+        o = oracle.GoOracle(1, N, superko="mask")
+        for a in seq:
+            want = [1 if (ref.legal(x) and not ref.recreates(x)) else 0 for x in range(A)]
+            assert o.legal_mask()[0].tolist() == want
+            taken += sum(ref.mask()) - sum(want)
+            ref.step(a)
+            o.step([a])
+            assert o.export_state().board[0].tolist() == ref.board()
+            assert bool(o.terminated()[0]) == ref.terminated and o.rewards()[0].tolist() == ref.rewards
+            if ref.terminated:
+                break
+    assert taken > 0 or N > 2
+
+
+def test_mask_level_random_games_against_python():
+    rng = np.random.default_rng(23)
+    taken = played_forbidden = 0
+    for N in (3, 4, 5, 6):
+        for g in range(150 if N < 5 else 25):
+            ref = RefGame(N, superko=True)
+            o = oracle.GoOracle(1, N, seed=g, superko="mask")
+            ref.black_player = int(o.export_state().black_player[0])
+            while not ref.terminated:
+                want = [1 if (ref.legal(x) and not ref.recreates(x)) else 0 for x in range(N * N + 1)]
+                m = o.legal_mask()[0]
+                assert m.tolist() == want
+                forbidden = [x for x in range(N * N) if ref.legal(x) and ref.recreates(x)]
+                taken += len(forbidden)
+                if forbidden and rng.random() < 0.1:
+                    a = int(rng.choice(forbidden)); played_forbidden += 1     # now and then play a forbidden point: game over
+                else:
+                    legal = np.flatnonzero(m[:-1])
+                    a = int(rng.choice(legal)) if (len(legal) and rng.random() < 0.93) else N * N
+                ref.step(a)
+                o.step([a])
+                assert o.export_state().board[0].tolist() == ref.board()
+                assert bool(o.terminated()[0]) == ref.terminated and o.rewards()[0].tolist() == ref.rewards
+    assert taken >= 20 and played_forbidden >= 2
+
+
+@pytest.mark.parametrize("N,B,plies", [(5, 64, 60), (9, 24, 170)])
+def test_counted_comparison_equals_the_literal_one(N, B, plies):
+    """The mask uses the comparison that skips earlier positions with other stone counts; it must agree with the literal
+    comparison against every earlier position, point by point, and the two readings must differ only in the mask."""
+    seed = 3
+    o = oracle.GoOracle(B, N, seed=seed, superko="mask", auto_reset=True)
+    taken = 0
+    for t in range(plies):
+        st = o.export_state()
+        m = o.legal_mask()
+        for b in range(B):
+            simple = oracle.legal_chains(st.board[b], N, int(st.to_play[b]), int(st.ko[b]))
+            for p_ in np.flatnonzero(simple[:-1]):
+                rep = o.repeats_literal(b, int(p_))
+                assert m[b, p_] == (0 if rep else 1)
+                taken += rep
+            assert (m[b][simple == 0] == 0).all() and m[b, -1] == 1
+        o.step(o.random_actions(seed, t))
+    assert taken > 0 or N == 9                                                 # 9x9 games rarely offer a repeating play
+
+
+def test_the_two_readings_agree_on_what_is_a_violation():
+    seed, B = 5, 1024
+    a_ = oracle.GoOracle(B, 5, seed=seed, superko=True)                         # enforced at play time
+    b_ = oracle.GoOracle(B, 5, seed=seed, superko="mask")                        # honoured by the mask
+    differ = 0
+    for t in range(60):
+        act = a_.random_actions(seed, t)                                         # drawn from the simple-ko mask
+        ma, mb = a_.legal_mask(), b_.legal_mask()
+        assert (mb <= ma).all()
+        differ += int((ma != mb).sum())
+        a_.step(act); b_.step(act)
+        sa, sb = a_.export_state(), b_.export_state()
+        assert (sa.board == sb.board).all() and (a_.terminated() == b_.terminated()).all() and (a_.rewards() == b_.rewards()).all()
+        assert (a_.illegal_count() == b_.illegal_count()).all()
+    assert differ > 0 and a_.illegal_count().sum() > 0
