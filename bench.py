@@ -209,7 +209,8 @@ def main():
                          "step kernel per ply; rollout: --rollout-len plies per launch with the state kept in registers")
     ap.add_argument("--rollout-len", type=int, default=50, help="plies per launch in rollout mode")
     ap.add_argument("--rollout-slices", type=int, default=1, help="trajectory slices the rollout writes to (1 = overwrite one set of buffers)")
-    ap.add_argument("--superko", action="store_true", help="Go only: switch the positional-superko rule on (not the headline metric)")
+    ap.add_argument("--superko", type=int, default=0, choices=[0, 1, 2], help="Go only: positional superko, 2 = honoured by the legal mask (the rule "
+                                                                              "proper), 1 = enforced when the move is played (not the headline metric)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-obs", action="store_true", help="do not emit the observation (not the headline metric)")
     ap.add_argument("--ceilings", action="store_true", help="print the reference measurements of this configuration instead of the benchmark line")
@@ -264,7 +265,7 @@ class GoStepper:
         N = cfg.board_size
         self.env = pg.GoEnv(B, N, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
         if superko:
-            self.env.enable_superko()
+            self.env.enable_superko(int(superko))
         ids = None if B == cfg.batch else list(range(B))
         start = workloads.start_times(cfg, ids)
         self.start = None if start is None else torch.as_tensor(start, device="cuda")
@@ -329,7 +330,7 @@ def bench_go(args, cfg):
         assert K % Lr == 0, "--steps must be a multiple of --rollout-len"
         env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
         if args.superko:
-            env.enable_superko()
+            env.enable_superko(int(args.superko))
         import workloads
         start = workloads.start_times(cfg)
         start_dev = None if start is None else torch.as_tensor(start, device="cuda")
@@ -420,7 +421,7 @@ def bench_go(args, cfg):
         "dtype": "u32",
         "data": "synthetic",
         "config": {"workload": cfg.name, "board_size": N, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset,
-                   "observation": with_obs, "mode": args.mode, "superko": bool(args.superko), "komi": cfg.komi_x2 / 2,
+                   "observation": with_obs, "mode": args.mode, "superko": int(args.superko), "komi": cfg.komi_x2 / 2,
                    "pre_roll_plies": pre, "timed_ply_window": window,
                    "window_note": f"launch indices since init; plies 0..{pre - 1} are an untimed pre-roll through pgxgo_rollout (boards dense, games out "
                                   f"of step), then {Wm} untimed launches of the timed path",

@@ -169,17 +169,22 @@ int pgxgo_import_state(pgxgo_t h, const int8_t* board_dev, const int8_t* history
 int pgxgo_set_boards_per_wavefront(pgxgo_t h, int32_t boards);
 
 /* Positional superko (Appendix C "Go": Tromp-Taylor rules, whose repetition rule forbids a play that recreates an
- * earlier whole-board position of the game).  Off by default (simple ko only).  Reading: the rule is enforced when
- * the move is played -- a play that brings back a position the game has already shown is an illegal action (the
- * game ends, offender -1 / opponent +1, position unchanged) -- while the legal mask keeps showing the simple-ko set.
- * Positions are compared through 64-bit Zobrist keys kept in a per-game table inside table_dev.
- *   pgxgo_superko_bytes: bytes of device memory the tables need (0 for invalid arguments); 256-byte aligned.
- *   pgxgo_enable_superko: switches the rule on with a caller-owned buffer that must outlive the handle (or off with
- *     table_dev = NULL).  The positions known from then on are the ones the state still carries (the 8 history
- *     positions and the current one); the same holds after pgxgo_import_state.  Needs max_steps <= 2*N*N.
- *     While the rule is on, pgxgo_rollout, pgxgo_step_slots and pgxgo_copy_slots return PGXGO_EINVAL. */
+ * earlier whole-board position of the game).  Off by default (simple ko only, as the benchmark configurations state).
+ *   mode 2: the rule proper.  legal_action_mask leaves out every play that would recreate an earlier position of the
+ *           game; playing one anyway is an illegal action like any other (game over, offender -1 / opponent +1,
+ *           position unchanged).
+ *   mode 1: the rule is looked at only when the move is played (same consequence for the offender), while the mask
+ *           keeps showing the simple-ko set.
+ *   mode 0 (table_dev ignored): off.
+ * Positions are compared through their stone counts and 45 bits of a Zobrist key, kept in a per-game table inside
+ * table_dev.  pgxgo_superko_bytes: bytes of device memory the tables need (0 for invalid arguments); 256-byte aligned.
+ * pgxgo_enable_superko switches the rule on with a caller-owned buffer that must outlive the handle.  The positions
+ * known from then on are the ones the state still carries (the 8 history positions and the current one); the same
+ * holds after pgxgo_import_state.  Needs max_steps <= 2*N*N.  Every entry point honours the rule: pgxgo_step /
+ * pgxgo_step_sample, pgxgo_rollout, pgxgo_random_actions, the getters, and pgxgo_step_slots / pgxgo_copy_slots, where a
+ * game that moves to another slot takes its table along (16 KB per 19x19 game, 4 KB per 9x9 game). */
 size_t pgxgo_superko_bytes(int32_t batch, int32_t board_size);
-int pgxgo_enable_superko(pgxgo_t h, void* table_dev, size_t table_bytes);
+int pgxgo_enable_superko(pgxgo_t h, int32_t mode, void* table_dev, size_t table_bytes);
 
 /* Blocks the host until everything enqueued on the handle's stream has finished. */
 int pgxgo_sync(pgxgo_t h);

@@ -52,7 +52,7 @@ def lib():
         L.pgxgo_set_boards_per_wavefront.argtypes = [vp, i32]
         L.pgxgo_superko_bytes.restype = C.c_size_t
         L.pgxgo_superko_bytes.argtypes = [i32, i32]
-        L.pgxgo_enable_superko.argtypes = [vp, vp, C.c_size_t]
+        L.pgxgo_enable_superko.argtypes = [vp, i32, vp, C.c_size_t]
         for n in ("boards_per_wavefront", "num_actions", "obs_bytes"):
             getattr(L, "pgxgo_" + n).argtypes = [i32]
             getattr(L, "pgxgo_" + n).restype = i32
@@ -236,15 +236,18 @@ class GoEnv:
             _check(rc if rc < 0 else -1, "pgxgo_set_boards_per_wavefront")
         return rc
 
-    def enable_superko(self, on=True):
-        """Positional superko: a play that recreates an earlier position of the game becomes an illegal action."""
-        if not on:
-            _check(lib().pgxgo_enable_superko(self._h, None, 0), "pgxgo_enable_superko")
+    def enable_superko(self, mode=1):
+        """Positional superko.  "mask" / 2: the rule proper, the legal mask leaves out every play that would recreate an
+        earlier position of the game.  True / 1: looked at only when the move is played (the offender loses), the mask
+        keeps showing the simple-ko set.  False / 0: off."""
+        mode = 2 if mode == "mask" else int(mode)
+        if mode == 0:
+            _check(lib().pgxgo_enable_superko(self._h, 0, None, 0), "pgxgo_enable_superko")
             self._superko = None
             return
         nbytes = lib().pgxgo_superko_bytes(self.B, self.N)
         self._superko = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-        _check(lib().pgxgo_enable_superko(self._h, _ptr(self._superko), nbytes), "pgxgo_enable_superko")
+        _check(lib().pgxgo_enable_superko(self._h, mode, _ptr(self._superko), nbytes), "pgxgo_enable_superko")
 
     # ---- canonical state ------------------------------------------------------------------------------------
     STATE_FIELDS = (("board", torch.int8), ("history", torch.int8), ("ko", torch.int32), ("to_play", torch.int8),

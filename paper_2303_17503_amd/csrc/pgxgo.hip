@@ -690,24 +690,70 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
 
 // ------------------------------------------------------------------------------------------------
 // positional superko (Appendix C "Go": Tromp-Taylor rules, whose repetition rule forbids a play that recreates
-// an earlier whole-board position of the game).  Reading: enforced when the move is played -- the offender
-// loses like for any illegal action -- while the legal mask keeps showing the simple-ko set.
-// Every position is summarised by a 64-bit Zobrist key (XOR of one key per stone), updated incrementally from
-// the stones that changed; the keys of the positions a game has shown are kept in a per-game open-addressing
-// table in device memory (SLOTS entries of 8 bytes, linear probing, at most 2*N*N + 9 of them in use).
+// an earlier whole-board position of the game).  Two readings, chosen by `mode`: 2 = the rule proper, the legal mask
+// leaves such plays out; 1 = looked at only when the move is played (the offender loses like for any illegal
+// action) while the mask keeps showing the simple-ko set.
+//
+// Every position is summarised by a Zobrist key (XOR of one key per stone, updated from the stones that changed)
+// and its two stone counts.  A play by colour c always gives a position with exactly one more stone of colour c,
+// so the earlier positions a play can recreate are those whose count of c is (current count + 1): the per-game
+// table (open addressing, linear probing, 8-byte entries) holds every position twice, once on the probe chain of
+// (black, its black count) and once on that of (white, its white count).  Per ply that costs one chain look-up for
+// the played move, and one for the next mover's forbidden points, which is empty most of the time; only when an
+// earlier position with the right count exists is the set of plays that would recreate it worked out (the single
+// point whose key equals the key difference, or a capturing play whose captured chain has the right size and keys).
+// An entry = 45 key bits + both counts, so a false match needs equal counts and a 45-bit collision.
 // ------------------------------------------------------------------------------------------------
 template <int N>
 struct Zt {
-  static constexpr uint32_t SLOTS = N == 19 ? 2048u : 512u;
-  static_assert(SLOTS >= 2u * (2u * N * N + 9u), "the table stays at most half full");
+  static constexpr int LOG2 = N == 19 ? 11 : 9;
+  static constexpr uint32_t SLOTS = 1u << LOG2;
+  static constexpr uint32_t MASK = SLOTS - 1u;
+  static_assert(SLOTS > 2u * (2u * N * N + 9u), "two entries per position (ply cap + the imported history window) always leave empty slots");
 };
 
 __device__ __forceinline__ uint2 zkey(uint32_t point, uint32_t colour) {   // colour 0 black / 1 white
   const uint32_t lo = mixer(0x9E3779B9u * (2u * point + colour + 1u));
   return make_uint2(lo, mixer(lo + 0x85EBCA6Bu));
 }
-// the stored form of a position key: never (0,0), which marks an empty slot
-__device__ __forceinline__ uint2 zstored(uint2 k) { return make_uint2(k.x, k.y | 0x80000000u); }
+
+struct SkGame {   // key and stone counts of a game's current position (the same in every lane of the board)
+  uint2 key;
+  int nb, nw;
+};
+__device__ __forceinline__ SkGame sk_unpack(uint4 v) {
+  SkGame g;
+  g.key = make_uint2(v.x, v.y); g.nb = (int)(v.z & 0xFFFFu); g.nw = (int)(v.z >> 16);
+  return g;
+}
+__device__ __forceinline__ uint4 sk_pack(const SkGame& g) { return make_uint4(g.key.x, g.key.y, (uint32_t)g.nb | ((uint32_t)g.nw << 16), 0u); }
+
+// table entry of a position: key bits 0..44, black count, white count, and a top bit so that no entry is (0,0) = empty
+__device__ __forceinline__ uint2 sk_entry(uint2 key, int nb, int nw) {
+  return make_uint2(key.x, (key.y & 0x1FFFu) | ((uint32_t)nb << 13) | ((uint32_t)nw << 22) | 0x80000000u);
+}
+__device__ __forceinline__ bool sk_real(uint2 e) { return (e.y >> 31) != 0u; }
+__device__ __forceinline__ int sk_count(uint2 e, int colour) { return (int)((e.y >> (colour ? 22 : 13)) & 511u); }
+// start of the probe chain of the positions whose count of `colour` stones is `count`
+template <int N>
+__device__ __forceinline__ uint32_t sk_home(int colour, int count) {
+  return ((uint32_t)(2 * count + colour + 1) * 0x9E3779B1u) >> (32 - Zt<N>::LOG2);
+}
+// Table accesses go to the device-coherent level: a wavefront of the rollout kernel reads in a later ply what its own
+// lanes wrote in an earlier one.
+__device__ __forceinline__ uint2 tab_load(const uint2* p) {
+  const unsigned long long v = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint2((uint32_t)v, (uint32_t)(v >> 32));
+}
+__device__ __forceinline__ void tab_store(uint2* p, uint2 e) {
+  __hip_atomic_store((unsigned long long*)p, (unsigned long long)e.x | ((unsigned long long)e.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// orders a wavefront's earlier global-memory accesses before its later ones as seen by its own lanes
+__device__ __forceinline__ void wave_mem_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 // XOR of the keys of the stones (black bits, white bits) of row r
 template <int N>
@@ -732,43 +778,210 @@ __device__ __forceinline__ uint2 board_xor(const Lane<N>& L, uint2 v, uint32_t* 
   return out;
 }
 
-// Looks `key` up in the board's table (tab = this board's SLOTS entries), N consecutive slots per round, one per
-// row lane.  found: the key is in the table.  Otherwise free_slot = the first empty slot from the key's home
-// slot on, where an insert goes (ok = such a slot exists; always, since the table is never more than half full).
-// pre_e / pre_base: entries a caller has already loaded for the round that starts at slot pre_base (a guess of the
-// home slot made before the key was known); pre_base = ~0u when there are none.
+// number of set bits of a board-wide set given by its row words, known to every lane of the board
 template <int N>
-__device__ __forceinline__ void table_probe(const Lane<N>& L, const uint2* tab, uint2 key, bool active, uint32_t pre_base, uint2 pre_e, bool& found,
-                                            bool& ok, uint32_t& free_slot) {
+__device__ __forceinline__ int board_popcount(const Lane<N>& L, uint32_t w) {
+  const uint32_t v = __popc(w);
+  int sum = 0;
+#pragma unroll
+  for (int k = 0; (1 << k) <= N; ++k) {
+    const uint64_t mk = __ballot((v >> k) & 1u);
+    sum += (__popc((uint32_t)mk & L.seglo) + __popc((uint32_t)(mk >> 32) & L.seghi)) << k;
+  }
+  return sum;
+}
+
+// N consecutive table slots from `home`, one per row lane, loaded ahead of their use (home = ~0u: nothing loaded)
+struct SkWin {
+  uint32_t home;
+  uint2 e;
+};
+template <int N>
+__device__ __forceinline__ SkWin sk_window(const Lane<N>& L, const uint2* tab, uint32_t home, bool want) {
+  SkWin w;
+  w.home = want ? home : ~0u;
+  w.e = make_uint2(1u, 0u);   // neither empty nor a real entry
+  if (L.valid && want) w.e = tab_load(&tab[(home + (uint32_t)L.r) & Zt<N>::MASK]);
+  return w;
+}
+
+// Walks the probe chain that starts at `home` (the same for every lane of a board; active = this board takes part),
+// N slots per round, one per row lane, until the chain's first empty slot.  visit(e, look) is called once per round
+// by every lane of the wavefront with the lane's entry (look = the lane holds a slot of an active board's chain).
+// free_slot = the first empty slot other than `taken` (a slot this ply has filled already; ~0u = none); ok = found,
+// which is always the case since the table is never full.  pre: windows loaded earlier, used when they start at `home`.
+template <int N, class V>
+__device__ __forceinline__ void sk_walk(const Lane<N>& L, const uint2* tab, uint32_t home, bool active, const SkWin (&pre)[3], uint32_t taken,
+                                        V&& visit, bool& ok, uint32_t& free_slot) {
   using G = Geo<N>;
-  constexpr uint32_t MASK = Zt<N>::SLOTS - 1u;
   const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
-  found = false; ok = false; free_slot = 0u;
+  ok = false; free_slot = 0u;
   bool done = !active;
-  uint32_t base = key.x & MASK;
-  for (uint32_t round = 0; round < Zt<N>::SLOTS / N + 1u; ++round) {
+  uint32_t base = home;
+  for (uint32_t round = 0; round < Zt<N>::SLOTS / N + 2u; ++round) {
     if (__ballot(!done) == 0ull) break;
     const bool look = L.valid && !done;
-    uint2 e = make_uint2(1u, 1u);
+    uint2 e = make_uint2(1u, 0u);
     if (look) {
-      if (round == 0u && base == pre_base) e = pre_e;
-      else e = tab[(base + (uint32_t)L.r) & MASK];
+      const uint32_t slot = (base + (uint32_t)L.r) & Zt<N>::MASK;
+      if (round == 0u && pre[0].home == base) e = pre[0].e;
+      else if (round == 0u && pre[1].home == base) e = pre[1].e;
+      else if (round == 0u && pre[2].home == base) e = pre[2].e;
+      else e = tab_load(&tab[slot]);
+      if (slot == taken && (e.x | e.y) == 0u) e = make_uint2(1u, 0u);
     }
+    visit(e, look);
     const uint64_t em = __ballot(look && (e.x | e.y) == 0u) & seg;
-    const uint64_t mm = __ballot(look && e.x == key.x && e.y == key.y) & seg;
-    const int fe = em ? __ffsll((long long)em) - 1 : 64, fm = mm ? __ffsll((long long)mm) - 1 : 64;
     if (!done) {
-      if (fm < fe) { found = true; done = true; }
-      else if (fe < 64) { free_slot = (base + (uint32_t)(fe - (L.j * G::STRIDE + 1))) & MASK; ok = true; done = true; }
+      if (em) { free_slot = (base + (uint32_t)(__ffsll((long long)em) - 1 - (L.j * G::STRIDE + 1))) & Zt<N>::MASK; ok = true; done = true; }
       else base += N;
     }
   }
 }
 
-// One ply with the repetition rule.  Same steps as go_step_kernel; in addition the key of the position after the
-// move is looked up in the game's table before the move is accepted.
+// What a ply does to the game's key set (the same in every lane of the board).
+struct SkPly {
+  uint2 key;        // key and counts of the position after the ply (meaningful for a board that placed a stone)
+  int nb, nw;
+  uint2 entry;      // its table entry
+  bool found;       // that position is in the table already: the play is a repetition
+  bool ok;          // free_a is valid
+  uint32_t free_a;  // where the entry goes on the chain of the mover's colour
+};
+
+// After the rules have been applied to a board that placed a stone (colour c, stones `captured` taken): the new
+// position's key, counts and entry, whether the table holds it already, and the free slot on its first chain.
+template <int N>
+__device__ __forceinline__ SkPly sk_look(const Lane<N>& L, const uint2* tab, const SkGame& g, int c, const Move& mv, uint32_t captured,
+                                         const SkWin (&pre)[3], uint32_t* scratch) {
+  SkPly s;
+  const bool played = mv.playing;
+  const uint2 kp = zkey((uint32_t)(played ? mv.pr * N + mv.pc : 0), (uint32_t)c);
+  int ncap = 0;
+  uint2 dk = make_uint2(0u, 0u);
+  if (__ballot(captured != 0u) != 0ull) {   // the captured stones have the other colour
+    ncap = board_popcount<N>(L, captured);
+    dk = board_xor<N>(L, row_keys<N>(L.r, c ? captured : 0u, c ? 0u : captured), scratch);
+  }
+  const int own1 = (c ? g.nw : g.nb) + 1, opp1 = (c ? g.nb : g.nw) - ncap;
+  s.key = make_uint2(g.key.x ^ kp.x ^ dk.x, g.key.y ^ kp.y ^ dk.y);
+  s.nb = c ? opp1 : own1; s.nw = c ? own1 : opp1;
+  s.entry = sk_entry(s.key, s.nb, s.nw);
+  bool hit = false;
+  sk_walk<N>(L, tab, sk_home<N>(c, own1), played, pre, ~0u,
+             [&](uint2 e, bool look) { hit = hit || (look && e.x == s.entry.x && e.y == s.entry.y); }, s.ok, s.free_a);
+  s.found = played && board_any(hit, L.seglo, L.seghi);
+  return s;
+}
+
+// Writes the position of a board that placed a stone into the table (both chains) and makes it the game's current one.
+// tab_r: the table the chains are read from; tab_w: the one the entries go to (they differ only while the slot kernel
+// copies a game from one slot to another).
+template <int N>
+__device__ __forceinline__ void sk_insert(const Lane<N>& L, const uint2* tab_r, uint2* tab_w, uint4* zcur_of_board, SkGame& g, const SkPly& s, bool insert,
+                                          int c, const SkWin (&pre)[3]) {
+  if (__ballot(insert) == 0ull) return;
+  bool ok_c;
+  uint32_t free_c;
+  const int opp1 = c ? s.nb : s.nw;   // count of the colour that did not move
+  sk_walk<N>(L, tab_r, sk_home<N>(c ^ 1, opp1), insert, pre, s.ok ? s.free_a : ~0u, [](uint2, bool) {}, ok_c, free_c);
+  if (insert) { g.key = s.key; g.nb = s.nb; g.nw = s.nw; }
+  if (insert && L.valid && L.r == 0) {
+    if (s.ok) tab_store(&tab_w[s.free_a], s.entry);
+    if (ok_c) tab_store(&tab_w[free_c], s.entry);
+    *zcur_of_board = sk_pack(g);
+  }
+  wave_mem_fence();
+}
+
+// The plays of the mover (colour c2) that would recreate the earlier position with entry q (act = this board has such
+// an entry to look at), as row words.
+template <int N>
+__device__ __forceinline__ uint32_t sk_forbidden_by(const Lane<N>& L, const Row<N>& R, const SkGame& g, int c2, uint2 q, bool act, uint32_t legal_s,
+                                                    uint32_t capc, uint32_t* scratch) {
+  using G = Geo<N>;
+  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
+  const uint32_t dx = q.x ^ g.key.x, dy = (q.y ^ g.key.y) & 0x1FFFu;   // key of (earlier position) xor (current position)
+  const int diff = (c2 ? g.nb : g.nw) - sk_count(q, c2 ^ 1);           // stones of the other colour the play would have to take
+  const bool plain = act && diff == 0, taking = act && diff > 0;
+  uint32_t forb = 0u;
+  if (__ballot(plain) != 0ull) {   // a play that takes nothing: the two positions differ by that one stone
+    for (uint32_t d = plain ? (legal_s & ~capc) : 0u; d; d &= d - 1u) {
+      const uint2 k = zkey((uint32_t)(L.r * N + __ffs(d) - 1), (uint32_t)c2);
+      if (k.x == dx && (k.y & 0x1FFFu) == dy) forb |= d & (0u - d);
+    }
+  }
+  if (__ballot(taking) != 0ull) {  // a play that takes stones: try each of the board's capturing plays in turn
+    const uint32_t aopp = c2 ? R.ab : R.aw;
+    uint32_t rem = taking ? capc : 0u;
+    for (;;) {
+      const uint64_t nz = __ballot(rem != 0u);
+      if (nz == 0ull) break;
+      const uint64_t mine = nz & seg;
+      const bool on = mine != 0ull;
+      const int src = on ? (__ffsll((long long)mine) - 1) : L.lane;
+      const uint32_t low = rem & (0u - rem);
+      const uint32_t pb = (on && L.lane == src) ? low : 0u;            // the play as a row word of its board
+      const int pcol = __shfl((int)(__ffs(low) - 1), src);
+      const int prow = src - (L.j * G::STRIDE + 1);
+      const uint32_t taken = flood_plain(dilate(pb) & aopp, aopp);     // the chains in atari next to it
+      const int size = board_popcount<N>(L, taken);
+      const uint2 kt = board_xor<N>(L, row_keys<N>(L.r, c2 ? taken : 0u, c2 ? 0u : taken), scratch);
+      const uint2 kp = zkey((uint32_t)(on ? prow * N + pcol : 0), (uint32_t)c2);
+      if (on && size == diff && (kt.x ^ kp.x) == dx && ((kt.y ^ kp.y) & 0x1FFFu) == dy) forb |= pb;
+      rem &= ~pb;
+    }
+  }
+  return forb;
+}
+
+// The plays of the player to move that would recreate an earlier position of the game (row words): one walk of the
+// chain of the positions with one more stone of the mover's colour than now.
+template <int N>
+__device__ __forceinline__ uint32_t sk_forbidden(const Lane<N>& L, const uint2* tab, const SkGame& g, const Row<N>& R, const Meta& m, bool active,
+                                                 const SkWin (&pre)[3], uint32_t* scratch) {
+  uint32_t forb = 0u;
+  if (__ballot(active) == 0ull) return forb;
+  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
+  const int c2 = m.wtm, n2 = c2 ? g.nw : g.nb;
+  bool ok;
+  uint32_t fs;
+  sk_walk<N>(L, tab, sk_home<N>(c2, n2 + 1), active, pre, ~0u,
+             [&](uint2 e, bool look) {
+               uint64_t pend = __ballot(look && sk_real(e) && sk_count(e, c2) == n2 + 1);
+               if (pend == 0ull) return;          // nearly always: no earlier position has that count
+               const uint32_t legal_s = legal_row<N>(L, R, m.wtm, m.ko);
+               const uint32_t capc = legal_s & dilate(c2 ? R.ab : R.aw);   // plays that take stones: next to an opposing chain in atari
+               while (pend != 0ull) {             // one earlier position per board per turn
+                 const uint64_t mine = pend & seg;
+                 const bool act = mine != 0ull;
+                 const int src = act ? (__ffsll((long long)mine) - 1) : L.lane;
+                 const uint2 q = make_uint2((uint32_t)__shfl((int)e.x, src), (uint32_t)__shfl((int)e.y, src));
+                 pend &= ~__ballot(act && L.lane == src);
+                 forb |= sk_forbidden_by<N>(L, R, g, c2, q, act, legal_s, capc, scratch);
+               }
+             },
+             ok, fs);
+  return forb;
+}
+
+// all lanes of the wavefront clear the tables of the boards flagged by their row-0 lane (auto-reset); `game` = the
+// index of this lane's board among the handle's tables
+template <int N>
+__device__ __forceinline__ void sk_clear_tables(const Lane<N>& L, bool flagged, uint2* zt, uint4* zcur, int game) {
+  for (uint64_t q = __ballot(flagged && L.valid && L.r == 0); q; q &= q - 1ull) {
+    const size_t bb = (size_t)__shfl(game, __ffsll((long long)q) - 1);
+    uint4* t4 = (uint4*)(zt + bb * Zt<N>::SLOTS);
+    for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) t4[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (L.lane == 0) zcur[bb] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  wave_mem_fence();
+}
+
+// One ply with the repetition rule.  Same steps as go_step_kernel; in addition the position after the move is looked
+// up in the game's table before the move is accepted, and (mode 2) the next mover's repeating plays leave the mask.
 template <int N, bool TIGHT>
-__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint2* zcur) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur, int mode) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -781,7 +994,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   load_row<N>(a.planes, rows_total, L, R);
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
-  const uint2 hcur = L.boardok ? zcur[L.b] : make_uint2(0u, 0u);
+  SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
   fill_spread_table(lut);
   if (wave * a.wb >= a.B) return;
   const Row<N> R_loaded = R;
@@ -794,16 +1007,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
   const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
 
-  // The key of the position after the move = current key ^ key of the new stone ^ keys of the captured stones.
-  // Most moves capture nothing, so the table is read at the home slot of the first two terms before the rules run
-  // (the loads fly meanwhile) and read again only where stones were taken.
-  constexpr uint32_t ZMASK = Zt<N>::SLOTS - 1u;
-  const bool played = mv.playing;   // a pass shows no new position
-  const uint2 kp = zkey((uint32_t)(played ? mv.pr * N + mv.pc : 0), (uint32_t)m.wtm);
-  const uint2 hpred = make_uint2(hcur.x ^ kp.x, hcur.y ^ kp.y);
-  const uint32_t pre_base = hpred.x & ZMASK;
-  uint2 pre_e = make_uint2(1u, 1u);
-  if (played && L.valid) pre_e = tab[(pre_base + (uint32_t)L.r) & ZMASK];
+  // The three chains this ply may need start at slots known before the rules run when the move takes nothing (most do):
+  // the loads fly while the rules run.  pre[0]: positions with one more stone of the mover's colour (the played move's
+  // look-up and first insert; also the mover's own forbidden plays when the board does not move); pre[1]: one more
+  // stone of the other colour (the next mover's forbidden plays); pre[2]: as many stones of the other colour as now
+  // (second insert).
+  const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
+  SkWin pre[3];
+  pre[0] = sk_window<N>(L, tab, sk_home<N>(c, own + 1), L.boardok);
+  pre[1] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp + 1), L.boardok && mode == 2);
+  pre[2] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp), mv.playing);
 
   // the move is applied (captures included, no reset yet), then the new position is looked up
   Rules r0 = a.rules;
@@ -812,14 +1025,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   bool flag, reset;
   uint32_t captured;
   apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
-  const uint32_t gone_b = played ? (R_loaded.bk & ~R.bk) : 0u, gone_w = played ? (R_loaded.wt & ~R.wt) : 0u;
-  uint2 d = make_uint2(0u, 0u);
-  if (__ballot((gone_b | gone_w) != 0u) != 0ull) d = board_xor<N>(L, row_keys<N>(L.r, gone_b, gone_w), lds_mask_all[wib]);
-  const uint2 hnew = make_uint2(hpred.x ^ d.x, hpred.y ^ d.y);
-  bool found, ok;
-  uint32_t free_slot;
-  table_probe<N>(L, tab, zstored(hnew), played, pre_base, pre_e, found, ok, free_slot);
-  const bool violate = played && found;
+  const SkPly s = sk_look<N>(L, tab, g, c, mv, captured, pre, lds_mask_all[wib]);
+  const bool violate = s.found;
   if (__ballot(violate) != 0ull) {   // rare: redo the ply of this wavefront's boards with the offending moves turned illegal
     R = R_loaded;
     m = m_loaded;
@@ -833,21 +1040,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   }
   // a8: auto-reset, here instead of inside apply_move; the game's table is cleared by the whole wavefront
   const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
-  if (played && !violate && !do_reset && ok && L.valid && L.r == 0) {
-    tab[free_slot] = zstored(hnew);
-    zcur[L.b] = hnew;
-  }
-  if (do_reset) reset_board<N>(L, R, m, a.rules.seed);
-  for (uint64_t q = __ballot(do_reset && L.valid && L.r == 0); q; q &= q - 1ull) {
-    const int jb = (__ffsll((long long)q) - 1) / G::STRIDE;
-    const size_t bb = (size_t)wave * a.wb + jb;
-    uint4* t4 = (uint4*)(zt + bb * Zt<N>::SLOTS);
-    for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) t4[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (L.lane == 0) zcur[bb] = make_uint2(0u, 0u);
-  }
+  sk_insert<N>(L, tab, tab, &zcur[L.boardok ? L.b : 0], g, s, mv.playing && !violate && !do_reset, c, pre);
+  uint32_t forb = 0u;
+  if (mode == 2) forb = sk_forbidden<N>(L, tab, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
+  if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
+  sk_clear_tables<N>(L, do_reset, zt, zcur, L.b);
 
   if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
   if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb, a.nt_store != 0);
   if (!skip) {
     if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
@@ -864,12 +1064,15 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
 // Fills the tables from what the state still carries: the 8 history positions and the current one (set-up, import).
 // The tables must have been cleared by an earlier launch.
 template <int N>
-__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, int B, uint2* zt, uint2* zcur) {
+__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, int B, uint2* zt, uint4* zcur) {
   __shared__ uint32_t scratch[64];
   const Lane<N> L(blockIdx.x, threadIdx.x, B);
   Row<N> R;
   load_row<N>(planes, (size_t)B * N, L, R);
   uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
+  SkWin none[3];
+  none[0].home = none[1].home = none[2].home = ~0u;
+  none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
   for (int i = 8; i >= 0; --i) {   // history position i-1 (oldest first), then i = 0: the current stones
     uint32_t black = R.bk, white = R.wt;
     if (i > 0) {
@@ -883,15 +1086,22 @@ __global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* pla
     }
     uint2 k = make_uint2(0u, 0u);
     if (L.valid) k = row_keys<N>(L.r, black, white);
-    k = board_xor<N>(L, k, scratch);
-    bool found, ok;
-    uint32_t free_slot;
-    table_probe<N>(L, tab, zstored(k), L.boardok, ~0u, make_uint2(1u, 1u), found, ok, free_slot);
+    SkGame g;
+    g.key = board_xor<N>(L, k, scratch);
+    g.nb = board_popcount<N>(L, black); g.nw = board_popcount<N>(L, white);
+    const uint2 entry = sk_entry(g.key, g.nb, g.nw);
+    bool hit = false, ok_a, ok_b;
+    uint32_t free_a, free_b;
+    sk_walk<N>(L, tab, sk_home<N>(0, g.nb), L.boardok, none, ~0u, [&](uint2 e, bool look) { hit = hit || (look && e.x == entry.x && e.y == entry.y); },
+               ok_a, free_a);
+    const bool found = board_any(hit, L.seglo, L.seghi);
+    sk_walk<N>(L, tab, sk_home<N>(1, g.nw), L.boardok && !found, none, ok_a ? free_a : ~0u, [](uint2, bool) {}, ok_b, free_b);
     if (L.valid && L.r == 0) {
-      if (!found && ok) tab[free_slot] = zstored(k);
-      if (i == 0) zcur[L.b] = k;
+      if (!found && ok_a) tab_store(&tab[free_a], entry);
+      if (!found && ok_b) tab_store(&tab[free_b], entry);
+      if (i == 0) zcur[L.b] = sk_pack(g);
     }
-    __threadfence();   // the next round's look-ups must see this insert
+    __threadfence();   // the next round's look-ups must see these inserts
   }
 }
 
@@ -917,10 +1127,14 @@ struct SlotArgs {
   uint8_t* obs;         // [n][obs_pitch] or null
   int64_t mask_pitch, obs_pitch;
   Rules rules;
+  uint2* zt;            // positional superko (SK kernels): per-slot tables, per-slot current keys, mode 1 / 2
+  uint4* zcur;
+  int sk_mode;
 };
 
-template <int N, bool TIGHT>
-__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(SlotArgs a) {
+// SK: the positional-superko rule is on; a game that moves to another slot takes its key table along.
+template <int N, bool TIGHT, bool SK>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots_kernel(SlotArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -950,7 +1164,47 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(S
   float rew0, rew1;
   bool flag, reset;
   uint32_t captured;
-  apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
+  uint32_t forb = 0u;
+  if constexpr (!SK) {
+    apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
+  } else {
+    const int sslot = L.boardok ? src : 0, dslot = L.boardok ? dst : 0;
+    SkGame g = sk_unpack(L.boardok ? a.zcur[sslot] : make_uint4(0u, 0u, 0u, 0u));
+    const uint2* tab_r = a.zt + (size_t)sslot * Zt<N>::SLOTS;   // nothing writes to a source slot's table during the call
+    uint2* tab_w = a.zt + (size_t)dslot * Zt<N>::SLOTS;
+    const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
+    SkWin pre[3];
+    pre[0] = sk_window<N>(L, tab_r, sk_home<N>(c, own + 1), L.boardok);
+    pre[1] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp + 1), L.boardok && a.sk_mode == 2);
+    pre[2] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp), mv.playing);
+    for (uint64_t q = __ballot(L.valid && L.r == 0 && src != dst); q; q &= q - 1ull) {   // all lanes copy one table after the other
+      const int ln = __ffsll((long long)q) - 1;
+      const uint4* from = (const uint4*)(a.zt + (size_t)__shfl(sslot, ln) * Zt<N>::SLOTS);
+      uint4* to = (uint4*)(a.zt + (size_t)__shfl(dslot, ln) * Zt<N>::SLOTS);
+      for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) to[i] = from[i];
+    }
+    const Row<N> R_loaded = R;
+    const Meta m_loaded = m;
+    Rules r0 = a.rules;
+    r0.auto_reset = 0;
+    apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
+    const SkPly s = sk_look<N>(L, tab_r, g, c, mv, captured, pre, lds_mask_all[wib]);
+    const bool violate = s.found;
+    if (__ballot(violate) != 0ull) {   // rare: redo the ply with the repeating plays turned illegal
+      R = R_loaded;
+      m = m_loaded;
+      Move mv2 = mv;
+      if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
+      apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
+    }
+    const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
+    __threadfence();   // the copied tables are in place before entries are added to them or they are cleared
+    sk_insert<N>(L, tab_r, tab_w, &a.zcur[dslot], g, s, mv.playing && !violate && !do_reset, c, pre);
+    if (a.sk_mode == 2) forb = sk_forbidden<N>(L, tab_r, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
+    if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
+    sk_clear_tables<N>(L, do_reset, a.zt, a.zcur, dslot);
+    if (L.valid && L.r == 0 && !do_reset) a.zcur[dslot] = sk_pack(g);
+  }
   if ((threadIdx.x & 63) == L.j * G::STRIDE + 1 && L.j < G::W && L.b < a.n) {   // row-0 lane of the entry, inert or not
     if (bad) { if (a.term) a.term[L.b] = 255; }
     else {
@@ -959,7 +1213,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_slots_kernel(S
       if (a.term) a.term[L.b] = (uint8_t)(skip ? m.term : (flag ? 1 : 0));
     }
   }
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
   if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
   if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
   store_row<N>(a.planes, rows_total, L, R);
@@ -987,10 +1241,13 @@ struct RolloutArgs {
   uint8_t* mask;        // [slices][B][mask_pitch] or null
   uint8_t* obs;         // [slices][B][obs_pitch] or null
   int64_t mask_pitch, obs_pitch;
+  uint2* zt;            // positional superko (SK kernels): per-game tables, per-game current keys, mode 1 / 2
+  uint4* zcur;
+  int sk_mode;
 };
 
-template <int N, bool TIGHT>
-__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(RolloutArgs a) {
+template <int N, bool TIGHT, bool SK>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_kernel(RolloutArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -1007,6 +1264,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
   Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
   const int64_t start = (L.boardok && a.start_t) ? (int64_t)a.start_t[L.b] : INT64_MIN;
   uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  SkGame g;
+  uint2* tab = nullptr;
+  SkWin pre[3];
+  if constexpr (SK) {
+    g = sk_unpack(L.boardok ? a.zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
+    tab = a.zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
+    pre[0].home = pre[1].home = pre[2].home = ~0u;
+    pre[0].e = pre[1].e = pre[2].e = make_uint2(1u, 0u);
+    if (a.sk_mode == 2) legal &= ~sk_forbidden<N>(L, tab, g, R, m, L.boardok, pre, lds_mask_all[wib]);
+  }
   int slice = 0;
   for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
     const uint32_t t = a.t0 + (uint32_t)i;
@@ -1015,8 +1282,39 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
     const bool skip = !L.boardok || wait;
     float rew0, rew1;
     bool flag;
-    step_core<N, false>(L, R, m, a.rules, skip, d.pass, d.point, d.pr, d.pc, rew0, rew1, flag);
-    legal = legal_row<N>(L, R, m.wtm, m.ko);
+    if constexpr (!SK) {
+      step_core<N, false>(L, R, m, a.rules, skip, d.pass, d.point, d.pr, d.pc, rew0, rew1, flag);
+      legal = legal_row<N>(L, R, m.wtm, m.ko);
+    } else {
+      const Move mv = gate_move<N, false>(L, R, m, skip, d.pass, d.point, d.pr, d.pc);
+      const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
+      pre[0] = sk_window<N>(L, tab, sk_home<N>(c, own + 1), L.boardok);
+      pre[1] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp + 1), L.boardok && a.sk_mode == 2);
+      pre[2] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp), mv.playing);
+      const Row<N> R_before = R;
+      const Meta m_before = m;
+      Rules r0 = a.rules;
+      r0.auto_reset = 0;
+      bool reset;
+      uint32_t captured;
+      apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
+      const SkPly s = sk_look<N>(L, tab, g, c, mv, captured, pre, lds_mask_all[wib]);
+      const bool violate = s.found;   // possible only where the mask shows the simple-ko set (mode 1)
+      if (__ballot(violate) != 0ull) {
+        R = R_before;
+        m = m_before;
+        Move mv2 = mv;
+        if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
+        apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
+      }
+      const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
+      sk_insert<N>(L, tab, tab, &a.zcur[L.boardok ? L.b : 0], g, s, mv.playing && !violate && !do_reset, c, pre);
+      uint32_t forb = 0u;
+      if (a.sk_mode == 2) forb = sk_forbidden<N>(L, tab, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
+      if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
+      sk_clear_tables<N>(L, do_reset, a.zt, a.zcur, L.b);
+      legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
+    }
     const size_t sb = (size_t)slice * a.B;
     if (L.valid && L.r == 0) {
       const size_t e = sb + L.b;
@@ -1037,9 +1335,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_rollout_kernel(Roll
 // ------------------------------------------------------------------------------------------------
 // auxiliary kernels
 // ------------------------------------------------------------------------------------------------
-template <int N, bool TIGHT>
+// SK: the legal mask leaves out the plays that would recreate an earlier position (positional superko, mode 2)
+template <int N, bool TIGHT, bool SK>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint4* planes, const uint4* meta, int B, uint8_t* mask,
-                                                                      int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch) {
+                                                                      int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch, const uint2* zt,
+                                                                      const uint4* zcur) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -1052,15 +1352,26 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint
   Row<N> R;
   load_row<N>(planes, (size_t)B * N, L, R);
   Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  if constexpr (SK) {
+    if (mask) {
+      const SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
+      SkWin none[3];
+      none[0].home = none[1].home = none[2].home = ~0u;
+      none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
+      legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, lds_mask_all[wib]);
+    }
+  }
   emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
 }
 
 // k-th legal action of the current position, same row-per-lane mapping as the step kernel
-template <int N>
+template <int N, bool SK>
 __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(const uint4* planes, const uint4* meta, int B, uint32_t seed,
-                                                                                uint32_t t, const int32_t* start_t, int32_t* actions) {
+                                                                                uint32_t t, const int32_t* start_t, int32_t* actions, const uint2* zt,
+                                                                                const uint4* zcur) {
   using G = Geo<N>;
+  __shared__ uint32_t sk_scratch[SK ? kWavesPerBlock : 1][64];
   const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
   if (wave * G::W >= B) return;
   const Lane<N> L(wave, threadIdx.x & 63, B);
@@ -1080,7 +1391,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(
     R.bk = rec[0]; R.wt = rec[1]; R.ab = rec[2]; R.aw = rec[3];
   }
   Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
+  if constexpr (SK) {
+    const SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
+    SkWin none[3];
+    none[0].home = none[1].home = none[2].home = ~0u;
+    none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
+    legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, sk_scratch[threadIdx.x >> 6]);
+  }
   const bool wait = L.boardok && start_t && (int64_t)t < (int64_t)start_t[L.b];
   const Draw<N> d = draw_action<N>(L, legal, seed, t, wait);
   if (L.valid && L.r == 0) actions[L.b] = d.action();
@@ -1256,7 +1574,8 @@ struct pgxgo_ctx {
   float* rew_out;
   uint8_t* term_out;
   uint2* zt;     // positional superko: per-game key tables, or null when the rule is off
-  uint2* zcur;   // key of every game's current position
+  uint4* zcur;   // key and stone counts of every game's current position
+  int sk_mode;   // 0 off, 1 enforced when the move is played, 2 honoured by the legal mask
 };
 
 namespace {
@@ -1299,14 +1618,19 @@ int auto_boards_per_wavefront(int B) {
 template <int N>
 bool tight_pitches(const pgxgo_ctx* h) { return h->mask_pitch == Geo<N>::A && h->obs_pitch == Geo<N>::OBS; }
 
+template <int N, bool TIGHT, bool SK>
+void launch_emit_as(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {
+  hipLaunchKernelGGL((go_emit_kernel<N, TIGHT, SK>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
+                     h->mask_pitch, obs, h->obs_pitch, h->zt, h->zcur);
+}
+
 template <int N>
 int launch_emit(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {
-  if (tight_pitches<N>(h))
-    hipLaunchKernelGGL((go_emit_kernel<N, true>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
-                       h->mask_pitch, obs, h->obs_pitch);
-  else
-    hipLaunchKernelGGL((go_emit_kernel<N, false>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B, mask,
-                       h->mask_pitch, obs, h->obs_pitch);
+  const bool tight = tight_pitches<N>(h), sk = h->zt && h->sk_mode == 2;   // only then does the rule change the mask
+  if (tight && sk) launch_emit_as<N, true, true>(h, mask, obs);
+  else if (tight) launch_emit_as<N, true, false>(h, mask, obs);
+  else if (sk) launch_emit_as<N, false, true>(h, mask, obs);
+  else launch_emit_as<N, false, false>(h, mask, obs);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1326,8 +1650,8 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
     if (!sample) a.next_actions = nullptr;
-    if (tight) hipLaunchKernelGGL((go_step_superko_kernel<N, true>), grid, block, 0, h->stream, a, h->zt, h->zcur);
-    else hipLaunchKernelGGL((go_step_superko_kernel<N, false>), grid, block, 0, h->stream, a, h->zt, h->zcur);
+    if (tight) hipLaunchKernelGGL((go_step_superko_kernel<N, true>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+    else hipLaunchKernelGGL((go_step_superko_kernel<N, false>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
     HIPCHK(hipGetLastError());
     return PGXGO_OK;
   }
@@ -1341,24 +1665,36 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
 
 template <int N>
 int launch_random(pgxgo_ctx* h, uint32_t seed, uint32_t t, const int32_t* start_t, int32_t* actions) {
-  hipLaunchKernelGGL(go_random_actions_kernel<N>, dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B,
-                     seed, t, start_t, actions);
+  if (h->zt && h->sk_mode == 2)
+    hipLaunchKernelGGL((go_random_actions_kernel<N, true>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B,
+                       seed, t, start_t, actions, h->zt, h->zcur);
+  else
+    hipLaunchKernelGGL((go_random_actions_kernel<N, false>), dim3(blocks_for<N>(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, h->planes, h->meta, h->B,
+                       seed, t, start_t, actions, h->zt, h->zcur);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
 
 template <int N>
 int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
-  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_rollout_kernel<N, true>), dim3(blocks_for_wb(h->B, h->wb)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
-  else hipLaunchKernelGGL((go_rollout_kernel<N, false>), dim3(blocks_for_wb(h->B, h->wb)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
+  const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
+  if (tight && sk) hipLaunchKernelGGL((go_rollout_kernel<N, true, true>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_rollout_kernel<N, true, false>), grid, block, 0, h->stream, a);
+  else if (sk) hipLaunchKernelGGL((go_rollout_kernel<N, false, true>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_rollout_kernel<N, false, false>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
 
 template <int N>
 int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
-  if (tight_pitches<N>(h)) hipLaunchKernelGGL((go_step_slots_kernel<N, true>), dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
-  else hipLaunchKernelGGL((go_step_slots_kernel<N, false>), dim3(blocks_for<N>(a.n)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  const dim3 grid(blocks_for<N>(a.n)), block(64 * kWavesPerBlock);
+  const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
+  if (tight && sk) hipLaunchKernelGGL((go_step_slots_kernel<N, true, true>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false>), grid, block, 0, h->stream, a);
+  else if (sk) hipLaunchKernelGGL((go_step_slots_kernel<N, false, true>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_slots_kernel<N, false, false>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1382,7 +1718,7 @@ template <int N>
 size_t superko_bytes_for(int B, size_t* off_cur) {
   size_t o = align_up((size_t)B * Zt<N>::SLOTS * sizeof(uint2), 256);
   if (off_cur) *off_cur = o;
-  return o + align_up((size_t)B * sizeof(uint2), 256);
+  return o + align_up((size_t)B * sizeof(uint4), 256);
 }
 
 // clears the tables, then (rebuild) fills them from the history window of the current state
@@ -1513,7 +1849,7 @@ int pgxgo_step_sample(pgxgo_t h, const int32_t* actions_dev, uint32_t seed, uint
 
 int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint32_t t0, const int32_t* start_t_dev, int32_t* actions_dev,
                   float* rewards_dev, uint8_t* terminated_dev, uint8_t* mask_dev, uint8_t* obs_dev) {
-  if (!h || steps < 0 || slices < 1 || h->zt) return PGXGO_EINVAL;
+  if (!h || steps < 0 || slices < 1) return PGXGO_EINVAL;
   if (steps == 0) return PGXGO_OK;
   RolloutArgs a;
   a.planes = h->planes; a.meta = h->meta; a.B = h->B; a.wb = h->wb;
@@ -1522,17 +1858,19 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
   a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
+  a.zt = h->zt; a.zcur = h->zcur; a.sk_mode = h->sk_mode;
   return DISPATCH_N(h, launch_rollout<19>(h, a), launch_rollout<9>(h, a));
 }
 
 int pgxgo_step_slots(pgxgo_t h, int32_t n, const int32_t* src_slots_dev, const int32_t* actions_dev, const int32_t* dst_slots_dev,
                      uint8_t* mask_dev, uint8_t* obs_dev, float* rewards_dev, uint8_t* terminated_dev) {
-  if (!h || n < 0 || n > h->B || !src_slots_dev || !dst_slots_dev || h->zt) return PGXGO_EINVAL;
+  if (!h || n < 0 || n > h->B || !src_slots_dev || !dst_slots_dev) return PGXGO_EINVAL;
   if (n == 0) return PGXGO_OK;
   SlotArgs a;
   a.planes = h->planes; a.meta = h->meta; a.pool = h->B; a.n = n; a.src = src_slots_dev; a.dst = dst_slots_dev; a.actions = actions_dev;
   a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev; a.mask_pitch = h->mask_pitch; a.obs_pitch = h->obs_pitch;
   a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
+  a.zt = h->zt; a.zcur = h->zcur; a.sk_mode = h->sk_mode;
   return DISPATCH_N(h, launch_slots<19>(h, a), launch_slots<9>(h, a));
 }
 
@@ -1616,18 +1954,25 @@ size_t pgxgo_superko_bytes(int32_t batch, int32_t board_size) {
   return 0;
 }
 
-int pgxgo_enable_superko(pgxgo_t h, void* table_dev, size_t table_bytes) {
-  if (!h) return PGXGO_EINVAL;
-  if (!table_dev) { h->zt = nullptr; h->zcur = nullptr; return PGXGO_OK; }
-  if (((uintptr_t)table_dev & 255u) != 0 || h->max_steps > 2 * h->N * h->N) return PGXGO_EINVAL;
-  size_t off_cur;
-  const size_t need = h->N == 19 ? superko_bytes_for<19>(h->B, &off_cur) : superko_bytes_for<9>(h->B, &off_cur);
-  if (table_bytes < need) return PGXGO_EINVAL;
-  h->zt = (uint2*)table_dev;
-  h->zcur = (uint2*)((uint8_t*)table_dev + off_cur);
-  const int rc = DISPATCH_N(h, launch_superko_refresh<19>(h, true), launch_superko_refresh<9>(h, true));
-  if (rc != PGXGO_OK) { h->zt = nullptr; h->zcur = nullptr; }
-  return rc;
+int pgxgo_enable_superko(pgxgo_t h, int32_t mode, void* table_dev, size_t table_bytes) {
+  if (!h || mode < 0 || mode > 2) return PGXGO_EINVAL;
+  if (mode == 0 || !table_dev) {
+    if (mode != 0) return PGXGO_EINVAL;
+    h->zt = nullptr; h->zcur = nullptr; h->sk_mode = 0;
+  } else {
+    if (((uintptr_t)table_dev & 255u) != 0 || h->max_steps > 2 * h->N * h->N) return PGXGO_EINVAL;
+    size_t off_cur;
+    const size_t need = h->N == 19 ? superko_bytes_for<19>(h->B, &off_cur) : superko_bytes_for<9>(h->B, &off_cur);
+    if (table_bytes < need) return PGXGO_EINVAL;
+    h->zt = (uint2*)table_dev;
+    h->zcur = (uint4*)((uint8_t*)table_dev + off_cur);
+    h->sk_mode = mode;
+    const int rc = DISPATCH_N(h, launch_superko_refresh<19>(h, true), launch_superko_refresh<9>(h, true));
+    if (rc != PGXGO_OK) { h->zt = nullptr; h->zcur = nullptr; h->sk_mode = 0; return rc; }
+  }
+  // the bound mask follows the rule in force from now on
+  if (h->mask_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, nullptr), launch_emit<9>(h, h->mask_out, nullptr));
+  return PGXGO_OK;
 }
 
 int pgxgo_sync(pgxgo_t h) {

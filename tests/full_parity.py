@@ -36,7 +36,8 @@ def main():
     ap.add_argument("--plies", type=int, default=0, help="0 = warm-up + the configuration's measured plies")
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--state-every", type=int, default=100)
-    ap.add_argument("--superko", action="store_true", help="Go only: both sides with the positional-superko rule on")
+    ap.add_argument("--superko", type=int, default=0, help="Go only: both sides with the positional-superko rule on (1: enforced at play time, "
+                                                            "2: honoured by the legal mask)")
     ap.add_argument("--rollout", type=int, default=0, help="L > 0: use the rollout kernel, L plies per launch, every ply recorded in its own slice")
     ap.add_argument("--seed", type=int, default=None, help="another seed than the configuration's (more trajectories of the same shape)")
     a = ap.parse_args()
@@ -70,7 +71,7 @@ def run(args):
     env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset) if go else pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
     if args.superko:
         assert go, "the superko rule is a Go option"
-        env.enable_superko()
+        env.enable_superko(int(args.superko))
     mask, obs = env.new_mask(), env.new_obs()
     rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
     term = torch.zeros(B, dtype=torch.uint8, device="cuda")
@@ -83,7 +84,7 @@ def run(args):
     def make(lo, hi):
         ids = np.arange(lo, hi, dtype=np.int32)
         if go:
-            return oracle.GoOracle(hi - lo, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids, superko=args.superko)
+            return oracle.GoOracle(hi - lo, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, env_ids=ids, superko=int(args.superko))
         return hx.HexOracle(hi - lo, N, seed=seed, auto_reset=cfg.auto_reset, env_ids=ids)
 
     oracle.lib(); hx.lib()
@@ -133,7 +134,6 @@ def run(args):
 
     if args.rollout:
         L = args.rollout
-        assert not args.superko, "the rollout kernel does not carry the superko tables"
         tr = dict(actions=torch.empty((L, B), dtype=torch.int32, device="cuda"), rewards=torch.empty((L, B, 2), dtype=torch.float32, device="cuda"),
                   terminated=torch.empty((L, B), dtype=torch.uint8, device="cuda"), mask=torch.empty((L,) + tuple(mask.shape), dtype=torch.uint8, device="cuda"),
                   obs=torch.empty((L,) + tuple(obs.shape), dtype=torch.uint8, device="cuda"))
@@ -152,7 +152,7 @@ def run(args):
             env.step_sample(acts[t & 1], seed, t + 1, st_dev, out=acts[(t + 1) & 1])
             h_mask.copy_(mask); h_obs.copy_(obs); h_rew.copy_(rew); h_term.copy_(term)
             compare(t, with_state=(t % args.state_every == 0 or t == T - 1))
-    print(f"FULL PARITY OK: {cfg.name}{' with superko' if args.superko else ''}{' through the rollout kernel' if args.rollout else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
+    print(f"FULL PARITY OK: {cfg.name}{(' with superko (mode %d)' % int(args.superko)) if args.superko else ''}{' through the rollout kernel' if args.rollout else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
           f"reward and terminated flag compared; state every {args.state_every} plies; {len(shards)} oracle shards; {time.time() - t0:.0f} s", flush=True)
     pool.shutdown()
     return n_plies

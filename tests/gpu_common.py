@@ -24,7 +24,7 @@ class Pair:
         nb = batch if ids is None else len(ids)
         self.orc = oracle.GoOracle(nb, N, seed=seed, komi_x2=komi_x2, max_steps=max_steps, auto_reset=auto_reset, env_ids=self.ids, superko=superko)
         if superko:
-            self.env.enable_superko()
+            self.env.enable_superko(superko)     # True / 1: at play time; "mask" / 2: honoured by the legal mask
         self.sel = None if ids is None else torch.as_tensor(self.ids.astype(np.int64), device="cuda")
         self.bound = bind
         self.n_compared = 0      # environment-plies whose outputs were compared

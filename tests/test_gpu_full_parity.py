@@ -26,12 +26,21 @@ def test_every_environment_every_ply(game, config):
         assert n > 65536 * 500          # configuration 4: 500 measured plies plus each game's own warm-up
 
 
-@pytest.mark.parametrize("config", [1, 2, 3])
-def test_every_environment_every_ply_with_superko(config):
-    """The same with the positional-superko rule on (the oracle keeps every position of every game literally)."""
-    plies = 800 if config == 3 else 0            # the headline batch: the first 800 plies (the oracle's position lists are slow)
-    n = full_parity.run(full_parity.Args(game="go", config=config, superko=True, plies=plies))
-    assert n == (16384 * 800 if config == 3 else EXPECTED[("go", config)])
+@pytest.mark.parametrize("config,mode", [(1, 1), (2, 1), (3, 1), (1, 2), (2, 2), (3, 2)])
+def test_every_environment_every_ply_with_superko(config, mode):
+    """The same with the positional-superko rule on, enforced at play time (mode 1) and honoured by the legal mask (mode 2);
+    the oracle keeps every position of every game literally, and in mode 2 tries every legal point of every ply against
+    them, which bounds how many plies of the headline batch fit into the suite."""
+    plies = (800 if mode == 1 else 400) if config == 3 else 0
+    n = full_parity.run(full_parity.Args(game="go", config=config, superko=mode, plies=plies))
+    assert n == (16384 * plies if config == 3 else EXPECTED[("go", config)])
+
+
+@pytest.mark.parametrize("config", [1, 2])
+def test_every_environment_every_ply_with_superko_through_the_rollout_kernel(config):
+    """The rule proper through the rollout kernel, 8 plies per launch with every ply recorded in its own slice."""
+    n = full_parity.run(full_parity.Args(game="go", config=config, superko=2, rollout=8))
+    assert n == EXPECTED[("go", config)]
 
 
 @pytest.mark.parametrize("game,config", [("go", 1), ("go", 3), ("hex", 1)])

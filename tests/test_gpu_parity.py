@@ -457,9 +457,14 @@ def test_every_launch_shape(N, wb):
         p.orc.step(p.orc.random_actions(seed, t))
     g, c = p.env.export_state(), p.orc.export_state()
     assert (to_np(g["board"]) == c.board).all() and (to_np(g["history"]) == c.history).all() and (to_np(g["steps"]) == c.steps).all()
-    q = Pair(B, N, seed=seed, auto_reset=True, superko=True)
-    q.env.set_boards_per_wavefront(wb)
-    q.rollout(seed, 0, 90, fused=True, state_every=30)
+    for mode in (1, "mask"):
+        q = Pair(B, N, seed=seed, auto_reset=True, superko=mode)
+        q.env.set_boards_per_wavefront(wb)
+        q.rollout(seed, 0, 90, fused=True, state_every=30)
+        q.env.rollout(20, seed, 90)                            # the rollout kernel carries the key tables in every launch shape
+        for t in range(90, 110):
+            q.orc.step(q.orc.random_actions(seed, t))
+        q.rollout(seed, 110, 130, fused=True, state_every=10)
     with pytest.raises(pg.PgxGoError):
         p.env.set_boards_per_wavefront(7)
     assert p.env.set_boards_per_wavefront(0) == 1            # automatic choice for a batch this small
@@ -472,8 +477,9 @@ def test_tiny_batches(N, B):
     p = Pair(B, N, seed=70 + B, auto_reset=True)
     p.rollout(70 + B, 0, 2 * N * N + 40, fused=True, state_every=25)
     assert to_np(p.env.export_state()["episode"]).min() >= 1
-    q = Pair(B, N, seed=71, auto_reset=False, superko=True)
-    q.rollout(71, 0, 120, fused=False, state_every=30)
+    for mode in (1, "mask"):
+        q = Pair(B, N, seed=71, auto_reset=False, superko=mode)
+        q.rollout(71, 0, 120, fused=False, state_every=30)
     r = Pair(B, N, seed=72, auto_reset=True, bind=False)
     r.env.rollout(90, 72, 0)
     for t in range(90):

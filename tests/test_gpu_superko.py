@@ -1,5 +1,9 @@
-"""GPU parity of the positional-superko option (pgxgo_enable_superko) against the oracle's literal position
-history, bit-exact through the C ABI."""
+"""GPU parity of the positional-superko option (pgxgo_enable_superko; paper Appendix C "Go": Tromp-Taylor rules) against
+the oracle's literal position history, bit-exact through the C ABI, in both readings: mode 2 / "mask" = the rule proper
+(the legal mask leaves repeating plays out), mode 1 = enforced only when the move is played.  Through step,
+step_sample, random_actions, the getters, the rollout kernel and the slot API."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 import torch
@@ -11,6 +15,8 @@ from gpu_common import Pair, to_np
 pytestmark = pytest.mark.gpu
 
 N9 = 9
+MODES = [1, "mask"]
+FIELDS = ("board", "history", "ko", "to_play", "steps", "passes", "terminated", "black_player", "episode")
 
 
 def a9(r, c):
@@ -27,21 +33,29 @@ def step_all(p, action):
     p.step(torch.as_tensor(a, device="cuda"), a)
 
 
-@pytest.mark.parametrize("superko", [False, True])
+def import_both(p, s):
+    p.orc.import_state(s)
+    p.env.import_state({n: torch.as_tensor(np.ascontiguousarray(getattr(s, n)).astype(np.int32 if n == "episode" else getattr(s, n).dtype), device="cuda")
+                        for n in FIELDS})
+
+
+@pytest.mark.parametrize("superko", [False, 1, "mask"])
 def test_send_two_return_one(superko):
     p = Pair(7, N9, seed=1, auto_reset=False, superko=superko)
     for m in SEND_TWO:
         step_all(p, m)
         p.compare(f"move {m}", state=True)
-    assert to_np(p.mask)[:, RETURN_ONE].all()               # the mask shows the simple-ko set either way
+    assert to_np(p.mask)[:, RETURN_ONE].all() == (superko != "mask")        # only the rule proper takes it out of the mask
+    assert (to_np(p.env.legal_mask())[:, RETURN_ONE] == to_np(p.mask)[:, RETURN_ONE]).all()
     step_all(p, RETURN_ONE)
     p.compare("the returning stone", state=True)
-    assert to_np(p.term).all() == superko
-    assert (to_np(p.env.export_state()["illegal"]) == int(superko)).all()
+    assert to_np(p.term).all() == bool(superko)
+    assert (to_np(p.env.export_state()["illegal"]) == int(bool(superko))).all()
 
 
-def test_auto_reset_clears_the_table():
-    p = Pair(5, N9, seed=2, auto_reset=True, superko=True)
+@pytest.mark.parametrize("superko", MODES)
+def test_auto_reset_clears_the_table(superko):
+    p = Pair(5, N9, seed=2, auto_reset=True, superko=superko)
     for rnd in range(3):                                       # the same cycle in three consecutive games
         for m in SEND_TWO + [RETURN_ONE]:
             step_all(p, m)
@@ -51,19 +65,87 @@ def test_auto_reset_clears_the_table():
     assert (to_np(st["episode"]) == 3).all() and (to_np(st["illegal"]) == 3).all()
 
 
+def hand_history(B, cur, earlier, to_play):
+    """State whose current board is `cur` and whose previous position (one ply ago) is `earlier` (dicts point -> colour)."""
+    s = oracle.State(B, N9 * N9)
+    for p, v in cur.items():
+        s.board[:, p] = v
+    s.history[:, 0] = s.board
+    for p, v in earlier.items():
+        s.history[:, 1, p] = v
+    s.ko[:] = -1; s.to_play[:] = to_play; s.steps[:] = 20
+    return s
+
+
+@pytest.mark.parametrize("superko", MODES)
+def test_repeating_play_that_captures_nothing(superko):
+    """The earlier position is the current one plus a black stone on (4,4): Black's play there would bring it back."""
+    B = 8
+    cur = {a9(2, 2): 1, a9(6, 6): -1, a9(3, 7): -1}
+    earlier = dict(cur); earlier[a9(4, 4)] = 1
+    for to_play in (1, -1):                                      # White's stone on the same point gives another position
+        p = Pair(B, N9, seed=4, auto_reset=False, superko=superko)
+        import_both(p, hand_history(B, cur, earlier, to_play))
+        p.compare("after import", state=True)
+        expect_legal = not (superko == "mask" and to_play == 1)
+        assert to_np(p.mask)[:, a9(4, 4)].all() == expect_legal and to_np(p.mask)[:, a9(4, 5)].all()
+        a = np.array([a9(4, 4), a9(4, 5), a9(4, 4), 81, a9(4, 4), a9(0, 0), a9(4, 4), a9(4, 4)], np.int32)
+        p.step(torch.as_tensor(a, device="cuda"), a)
+        p.compare("after the play", state=True)
+        assert (to_np(p.term)[a == a9(4, 4)] == (1 if to_play == 1 else 0)).all()
+
+
+@pytest.mark.parametrize("superko", MODES)
+def test_repeating_play_that_captures(superko):
+    """White (0,0),(0,1) have their last liberty at (0,2); Black takes them there.  An earlier position equal to the result
+    makes that capture a repetition; one that differs in a single stone does not."""
+    B = 6
+    cur = {a9(0, 0): -1, a9(0, 1): -1, a9(1, 0): 1, a9(1, 1): 1, a9(7, 7): -1}
+    after = {a9(1, 0): 1, a9(1, 1): 1, a9(7, 7): -1, a9(0, 2): 1}
+    near = dict(after); near[a9(0, 1)] = -1
+    for earlier, repeats in ((after, True), (near, False)):
+        p = Pair(B, N9, seed=5, auto_reset=True, superko=superko)
+        import_both(p, hand_history(B, cur, earlier, 1))
+        p.compare("after import", state=True)
+        assert to_np(p.mask)[:, a9(0, 2)].all() == (not (repeats and superko == "mask"))
+        step_all(p, a9(0, 2))
+        p.compare("after the capture", state=True)
+        assert to_np(p.term).all() == repeats
+
+
+@pytest.mark.parametrize("superko", MODES)
 @pytest.mark.parametrize("N,B,plies,fused", [(9, 2048, 420, True), (9, 777, 300, False), (19, 96, 900, True)])
-def test_random_rollouts(N, B, plies, fused):
-    p = Pair(B, N, seed=11, auto_reset=True, superko=True)
+def test_random_rollouts(N, B, plies, fused, superko):
+    p = Pair(B, N, seed=11, auto_reset=True, superko=superko)
     p.rollout(11, 0, plies, fused=fused, state_every=25)
-    if N == 9:
+    if N == 9 and superko == 1:
         assert int(to_np(p.env.export_state()["illegal"]).sum()) > 0    # the rule did end some games
+    if superko == "mask":
+        assert int(to_np(p.env.export_state()["illegal"]).sum()) == 0   # the mask never offers a repeating play
+
+
+def test_the_mask_differs_from_the_simple_ko_mask_now_and_then():
+    """Same play with the rule proper and without: masks agree except where a repeating play is on offer."""
+    B, seed = 4096, 5
+    a_ = pg.GoEnv(B, 9, seed=seed, auto_reset=True)
+    b_ = pg.GoEnv(B, 9, seed=seed, auto_reset=True)
+    b_.enable_superko("mask")
+    taken = 0
+    for t in range(200):
+        act = b_.random_actions(seed, t)         # legal under both rules
+        a_.step(act); b_.step(act)
+        ma, mb = a_.legal_mask(), b_.legal_mask()
+        assert bool((mb <= ma).all())
+        taken += int((ma != mb).sum())
+    assert taken > 0
+    assert (to_np(a_.export_state()["board"]) == to_np(b_.export_state()["board"])).all()
 
 
 def test_same_play_without_the_rule_differs_only_at_violations():
     B, seed = 4096, 5
     a_ = pg.GoEnv(B, 9, seed=seed)
     b_ = pg.GoEnv(B, 9, seed=seed)
-    b_.enable_superko()
+    b_.enable_superko(1)
     for t in range(162):
         act = a_.random_actions(seed, t)
         a_.step(act); b_.step(act)
@@ -73,24 +155,20 @@ def test_same_play_without_the_rule_differs_only_at_violations():
     assert (to_np(sa["board"])[~hit] == to_np(sb["board"])[~hit]).all()
 
 
-def test_padded_pitches():
-    p = Pair(50, N9, seed=3, auto_reset=True, superko=True, obs_pitch=81 * 17 + 7, mask_pitch=96)
+@pytest.mark.parametrize("superko", MODES)
+def test_padded_pitches(superko):
+    p = Pair(50, N9, seed=3, auto_reset=True, superko=superko, obs_pitch=81 * 17 + 7, mask_pitch=96)
     p.rollout(3, 0, 250, fused=True, state_every=50)
 
 
-def test_import_rebuilds_from_the_history_window():
+@pytest.mark.parametrize("superko", MODES)
+def test_import_rebuilds_from_the_history_window(superko):
     src = oracle.GoOracle(3, N9)
     for m in SEND_TWO:
         src.step(np.full(3, m, np.int32))
     s = src.export_state()
-    p = Pair(3, N9, seed=0, auto_reset=False, superko=True)
-    p.orc.import_state(s)
-    p.env.import_state({"board": torch.as_tensor(s.board, device="cuda"), "history": torch.as_tensor(s.history, device="cuda"),
-                        "ko": torch.as_tensor(s.ko, device="cuda"), "to_play": torch.as_tensor(s.to_play, device="cuda"),
-                        "steps": torch.as_tensor(s.steps, device="cuda"), "passes": torch.as_tensor(s.passes, device="cuda"),
-                        "terminated": torch.as_tensor(s.terminated, device="cuda"),
-                        "black_player": torch.as_tensor(s.black_player, device="cuda"),
-                        "episode": torch.as_tensor(s.episode.astype(np.int32), device="cuda")})
+    p = Pair(3, N9, seed=0, auto_reset=False, superko=superko)
+    import_both(p, s)
     p.compare("after import", state=True)
     a = np.array([RETURN_ONE, a9(4, 4), RETURN_ONE], np.int32)
     p.step(torch.as_tensor(a, device="cuda"), a)
@@ -98,26 +176,30 @@ def test_import_rebuilds_from_the_history_window():
     assert to_np(p.term).tolist() == [1, 0, 1]
 
 
-def test_switching_on_mid_game_and_off_again():
+@pytest.mark.parametrize("superko", MODES)
+def test_switching_on_mid_game_and_off_again(superko):
     p = Pair(4, N9, seed=6, auto_reset=False)
     for m in SEND_TWO:
         step_all(p, m)
-    p.env.enable_superko(); p.orc.set_superko(True)
+    p.env.enable_superko(superko); p.orc.set_superko(superko)
+    p.compare("rule switched on: the bound mask follows", state=True)
     a = np.array([RETURN_ONE, RETURN_ONE, a9(6, 6), 81], np.int32)
     p.step(torch.as_tensor(a, device="cuda"), a)
     p.compare("rule switched on two plies before the repeat", state=True)
     assert to_np(p.term).tolist() == [1, 1, 0, 0]
-    q = Pair(2, N9, seed=6, auto_reset=False, superko=True)
+    q = Pair(2, N9, seed=6, auto_reset=False, superko=superko)
     for m in SEND_TWO:
         step_all(q, m)
-    q.env.enable_superko(False); q.orc.set_superko(False)
+    q.env.enable_superko(0); q.orc.set_superko(0)
+    q.compare("rule switched off: the bound mask follows", state=True)
     step_all(q, RETURN_ONE)
     q.compare("rule switched off", state=True)
     assert not to_np(q.term).any()
 
 
-def test_reset_with_the_rule_on():
-    p = Pair(6, N9, seed=8, auto_reset=False, superko=True)
+@pytest.mark.parametrize("superko", MODES)
+def test_reset_with_the_rule_on(superko):
+    p = Pair(6, N9, seed=8, auto_reset=False, superko=superko)
     for m in SEND_TWO:
         step_all(p, m)
     p.env.reset(); p.orc.reset()
@@ -131,23 +213,133 @@ def test_reset_with_the_rule_on():
     assert to_np(p.term).all()
 
 
-def test_other_entry_points_refuse_while_the_rule_is_on():
-    env = pg.GoEnv(8, 9, seed=1)
-    env.enable_superko()
-    idx = torch.arange(4, dtype=torch.int32, device="cuda")
-    with pytest.raises(pg.PgxGoError):
-        env.rollout(3, 1, 0)
-    with pytest.raises(pg.PgxGoError):
-        env.copy_slots(idx, idx)
-    env.enable_superko(False)
-    env.rollout(3, 1, 0)
+@pytest.mark.parametrize("superko", MODES)
+@pytest.mark.parametrize("N,B,T,stagger", [(9, 1500, 330, False), (9, 700, 200, True), (19, 60, 800, False)])
+def test_rollout_kernel_with_the_rule_on(N, B, T, stagger, superko):
+    """pgxgo_rollout carries the key tables: launches of L plies with every ply in its own slice against ply-by-ply oracle
+    stepping (drawn action, mask, observation, rewards, terminated), state after every launch."""
+    seed, L_ = 17, 10
+    p = Pair(B, N, seed=seed, auto_reset=True, superko=superko, bind=False)
+    start = (np.arange(B) % 37 - 5).astype(np.int32) if stagger else None
+    st = None if start is None else torch.as_tensor(start, device="cuda")
+    P = N * N
+    tr = dict(actions=torch.empty((L_, B), dtype=torch.int32, device="cuda"), rewards=torch.empty((L_, B, 2), dtype=torch.float32, device="cuda"),
+              terminated=torch.empty((L_, B), dtype=torch.uint8, device="cuda"), mask=torch.empty((L_, B, P + 1), dtype=torch.uint8, device="cuda"),
+              obs=torch.empty((L_, B, P * 17), dtype=torch.uint8, device="cuda"))
+    for t0 in range(0, T, L_):
+        p.env.rollout(L_, seed, t0, start_t=st, slices=L_, **tr)
+        got = {k: to_np(v) for k, v in tr.items()}
+        for i in range(L_):
+            a = p.orc.random_actions(seed, t0 + i, start)
+            assert (got["actions"][i] == a).all(), f"action t={t0 + i}"
+            p.orc.step(a)
+            live = a >= 0
+            assert (got["mask"][i] == p.orc.legal_mask()).all(), f"mask t={t0 + i}"
+            assert (got["obs"][i].reshape(B, N, N, 17) == p.orc.observe()).all(), f"observation t={t0 + i}"
+            assert got["rewards"][i][live].tobytes() == p.orc.rewards()[live].tobytes(), f"rewards t={t0 + i}"
+            assert (got["terminated"][i][live] == p.orc.terminated()[live]).all(), f"terminated t={t0 + i}"
+        g, c = p.env.export_state(), p.orc.export_state()
+        for name in FIELDS:
+            assert (to_np(g[name]).astype(np.int64) == getattr(c, name).astype(np.int64)).all(), (name, t0)
+        assert (to_np(g["illegal"]).astype(np.int64) == p.orc.illegal_count().astype(np.int64)).all()
+    if N == 9:
+        assert int(p.orc.illegal_count().sum()) > 0 if superko == 1 else int(p.orc.illegal_count().sum()) == 0
+    # stepping on after the launches uses the tables the rollout kernel left behind
+    p.rollout(seed, T, T + 40, start_t=start, fused=True, state_every=10)
 
 
-def test_headline_shape_with_the_rule_on():
+@pytest.mark.parametrize("superko", MODES)
+def test_slot_api_carries_the_tables(superko):
+    """step_slots / copy_slots with the rule on: a game that moves to another slot takes its position history along.
+    Oracle side: a slot is the list of actions that produced its game (plus the slot it started in, which fixes the
+    seats); an entry src -> dst is checked by replaying the source's list into a fresh single-game oracle, whose literal
+    position list is then the game's whole history."""
+    N, pool, seed = 9, 256, 9
+    rng = np.random.default_rng(5)
+    env = pg.GoEnv(pool, N, seed=seed, auto_reset=False)
+    env.enable_superko(superko)
+    P = N * N
+    games = [[] for _ in range(pool)]
+    root = list(range(pool))
+    for m in SEND_TWO:                                           # the first half of the pool starts one play away from a repetition
+        a = np.where(np.arange(pool) < pool // 2, m, -1).astype(np.int32)
+        env.step(torch.as_tensor(a, device="cuda"))
+        for d in range(pool // 2):
+            games[d].append(m)
+
+    def replay(actions, root_slot):
+        o = oracle.GoOracle(1, N, seed=seed, superko=superko, env_ids=np.array([root_slot], np.int32))
+        for a in actions:
+            o.step([a])
+        return o
+
+    ex = ThreadPoolExecutor(16)
+    by_rule = 0
+    for it in range(50):
+        n = int(rng.integers(60, pool // 2))
+        perm = rng.permutation(pool)
+        dst = perm[:n].astype(np.int32)
+        src = rng.choice(perm[n:], n).astype(np.int32)
+        same = rng.random(n) < 0.4
+        src = np.where(same, dst, src).astype(np.int32)
+        orcs = list(ex.map(lambda i: replay(games[src[i]], root[src[i]]), range(n)))
+        masks = np.stack([o.legal_mask()[0] for o in orcs])
+        simple = np.stack([oracle.legal_chains(o.export_state().board[0], N, int(o.export_state().to_play[0]), int(o.export_state().ko[0])) for o in orcs])
+        terminated = np.array([o.export_state().terminated[0] for o in orcs])
+        pick = (rng.random(masks.shape) * masks).argmax(axis=1).astype(np.int32)
+        kind = rng.integers(0, 10, n)
+        act = pick.copy()
+        act = np.where(kind == 6, rng.integers(0, P, n), act)         # any point: maybe illegal
+        act = np.where(kind == 7, RETURN_ONE, act)                    # the returning stone: a repetition while the corner is as it was
+        act = np.where(kind == 8, -1, act).astype(np.int32)           # plain copy
+        g_mask = torch.full((n, P + 1), 9, dtype=torch.uint8, device="cuda")
+        g_obs = torch.full((n, P * 17), 9, dtype=torch.uint8, device="cuda")
+        g_rew = torch.full((n, 2), 9.0, dtype=torch.float32, device="cuda")
+        g_term = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+        env.step_slots(torch.as_tensor(src, device="cuda"), torch.as_tensor(act, device="cuda"), torch.as_tensor(dst, device="cuda"),
+                       mask=g_mask, obs=g_obs, rewards=g_rew, terminated=g_term)
+        gm, go, gr, gt = to_np(g_mask), to_np(g_obs), to_np(g_rew), to_np(g_term)
+        staged = {}
+        for i, o in enumerate(orcs):
+            before = int(o.illegal_count()[0])
+            if act[i] != -1:
+                o.step([int(act[i])])
+            assert (gm[i] == o.legal_mask()[0]).all(), (it, i, "mask")
+            assert (go[i].reshape(N, N, 17) == o.observe()[0]).all(), (it, i, "observation")
+            if act[i] == -1:
+                assert (gr[i] == 0).all() and gt[i] == terminated[i], (it, i)
+            else:
+                assert gr[i].tobytes() == o.rewards()[0].tobytes() and gt[i] == o.terminated()[0], (it, i)
+                if not terminated[i] and act[i] < P and simple[i, act[i]] == 1 and int(o.illegal_count()[0]) > before:
+                    by_rule += 1                                      # legal by the simple rules, yet an illegal action: the repetition rule
+            stepped = act[i] != -1 and not terminated[i]
+            staged[int(dst[i])] = (games[src[i]] + ([int(act[i])] if stepped else []), root[src[i]])
+        by_rule += int((masks != simple).sum()) if superko == "mask" else 0
+        for d, (gl, r) in staged.items():
+            games[d] = gl; root[d] = r
+        if it % 10 == 9:                                              # the whole pool's boards now and then
+            boards = to_np(env.export_state()["board"])
+            for d in range(pool):
+                assert (boards[d] == replay(games[d], root[d]).export_state().board[0]).all(), (it, d)
+    # copy_slots moves the tables too: the copy of a game one play away from a repetition still knows it
+    srcs = np.array([d for d in range(pool) if games[d] == SEND_TWO][:8], np.int32)
+    if len(srcs):
+        free = np.array([d for d in range(pool) if d not in set(srcs.tolist())][:len(srcs)], np.int32)
+        env.copy_slots(torch.as_tensor(srcs, device="cuda"), torch.as_tensor(free, device="cuda"))
+        term = torch.zeros(len(free), dtype=torch.uint8, device="cuda")
+        env.step_slots(torch.as_tensor(free, device="cuda"), torch.full((len(free),), RETURN_ONE, dtype=torch.int32, device="cuda"),
+                       torch.as_tensor(free, device="cuda"), terminated=term)
+        assert to_np(term).all()
+    assert by_rule > 0
+    ex.shutdown()
+
+
+@pytest.mark.parametrize("superko", MODES)
+def test_headline_shape_with_the_rule_on(superko):
     """19x19 x 16384 in the launch shape bench.py times, a seeded sample of environments replayed by the oracle."""
     import workloads
     cfg = workloads.CONFIGS[3]
     rng = np.random.default_rng(77)
     ids = np.unique(np.concatenate([[0, 1, 2, cfg.batch - 1, cfg.batch - 2], rng.integers(0, cfg.batch, 40)]))
-    p = Pair(cfg.batch, cfg.board_size, seed=cfg.seed, auto_reset=True, ids=ids, superko=True)
+    p = Pair(cfg.batch, cfg.board_size, seed=cfg.seed, auto_reset=True, ids=ids, superko=superko)
     p.rollout(cfg.seed, 0, 700, fused=True, every=1, state_every=100)

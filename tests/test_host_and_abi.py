@@ -92,7 +92,7 @@ def test_superko_entry_points_and_key_table():
     L = pg.lib()
     assert L.pgxgo_superko_bytes(0, 19) == 0 and L.pgxgo_superko_bytes(4, 13) == 0
     assert L.pgxgo_superko_bytes(100, 19) >= 100 * (2048 * 8 + 8) and L.pgxgo_superko_bytes(100, 9) >= 100 * (512 * 8 + 8)
-    assert L.pgxgo_enable_superko(None, None, 0) == -1
+    assert L.pgxgo_enable_superko(None, 2, None, 0) == -1
     # the position keys are one 64-bit word per (point, colour); their low halves must all differ, or two stones could cancel
     M = 0xFFFFFFFF
 
