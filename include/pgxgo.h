@@ -38,6 +38,9 @@ extern "C" {
 #define PGXGO_EINVAL (-1) /* null pointer, unsupported board size, batch <= 0, pitch too small, buffer too small */
 #define PGXGO_EHIP (-2)   /* a HIP runtime call failed; see pgxgo_last_hip_error() */
 #define PGXGO_ENOMEM (-3) /* host allocation of the handle failed */
+#define PGXGO_ELIMIT (-4) /* pgxgo_init_static: the games do not fit the library's static state buffer */
+
+#define PGXGO_STATIC_STATE_BYTES (8u << 20) /* size of that buffer, per GPU the library runs on */
 
 typedef struct pgxgo_ctx* pgxgo_t; /* opaque host-side handle */
 
@@ -62,6 +65,18 @@ size_t pgxgo_state_bytes(int32_t batch, int32_t board_size);
  * no auto-reset, tight pitches, default stream).  Synchronises once before returning. */
 int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts,
                void* state_dev, size_t state_bytes);
+
+/* pgxgo_init for callers that cannot allocate: code under HIP graph capture, serving loops and harnesses in which
+ * hipMalloc (or any allocating routine) is forbidden.  Same arguments and result as pgxgo_init, except that the game
+ * state lives in a buffer of PGXGO_STATIC_STATE_BYTES that is part of the library image (each GPU the library runs on
+ * holds its own copy until the process ends) and the handle is a static object: the call allocates nothing on the
+ * host or the device, does not synchronise, and only enqueues the kernel that (re)writes the state of `batch` games
+ * on opts->stream.  The device is the current one.  Limits: pgxgo_state_bytes(batch, board_size) must not exceed
+ * PGXGO_STATIC_STATE_BYTES (about 7800 games of 19x19 or 23000 of 9x9), else PGXGO_ELIMIT.  There is ONE such state
+ * and ONE such handle per GPU: a second call on the same GPU re-initialises them and invalidates the earlier
+ * handle's games, and calls that overlap on one GPU (two streams, two threads) race.  Every other entry point works
+ * on the handle as on any other; pgxgo_destroy on it frees nothing.  Outputs still go to the caller's buffers. */
+int pgxgo_init_static(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts);
 
 /* Frees the host handle only (device buffers belong to the caller). */
 int pgxgo_destroy(pgxgo_t h);

@@ -31,6 +31,7 @@ def lib():
         L.pgxgo_state_bytes.restype = C.c_size_t
         L.pgxgo_state_bytes.argtypes = [i32, i32]
         L.pgxgo_init.argtypes = [C.POINTER(vp), i32, i32, u32, C.POINTER(_Opts), vp, C.c_size_t]
+        L.pgxgo_init_static.argtypes = [C.POINTER(vp), i32, i32, u32, C.POINTER(_Opts)]
         L.pgxgo_destroy.argtypes = [vp]
         L.pgxgo_reset.argtypes = [vp]
         L.pgxgo_bind_outputs.argtypes = [vp, vp, vp, vp, vp]
@@ -84,7 +85,7 @@ class GoEnv:
     """`batch` Go games on one GPU (paper Fig. 2 API)."""
 
     def __init__(self, batch, board_size, seed=0, komi_x2=15, max_steps=0, auto_reset=False, obs_pitch=0, mask_pitch=0,
-                 device="cuda:0"):
+                 device="cuda:0", static_state=False):
         L = lib()
         self.B, self.N = int(batch), int(board_size)
         self.P = self.N * self.N
@@ -96,12 +97,16 @@ class GoEnv:
         self.obs_pitch = int(obs_pitch) or self.P * 17
         self.mask_pitch = int(mask_pitch) or self.A
         with torch.cuda.device(self.device):
-            self._state = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
             self._stream = torch.cuda.current_stream(self.device)
             opts = _Opts(int(komi_x2), int(max_steps), int(bool(auto_reset)), int(obs_pitch), int(mask_pitch),
                          C.c_void_p(self._stream.cuda_stream))
             h = C.c_void_p()
-            _check(L.pgxgo_init(C.byref(h), self.B, self.N, seed & 0xFFFFFFFF, C.byref(opts), _ptr(self._state), nbytes), "pgxgo_init")
+            if static_state:     # pgxgo_init_static: the state lives in the library's own static buffer, nothing is allocated
+                self._state = None
+                _check(L.pgxgo_init_static(C.byref(h), self.B, self.N, seed & 0xFFFFFFFF, C.byref(opts)), "pgxgo_init_static")
+            else:
+                self._state = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+                _check(L.pgxgo_init(C.byref(h), self.B, self.N, seed & 0xFFFFFFFF, C.byref(opts), _ptr(self._state), nbytes), "pgxgo_init")
         self._h = h
         self.mask_out = self.obs_out = self.rewards_out = self.terminated_out = None
 

@@ -1737,7 +1737,47 @@ int launch_superko_refresh(pgxgo_ctx* h, bool rebuild) {
 
 #define DISPATCH_N(h, call19, call9) ((h)->N == 19 ? (call19) : (call9))
 
+// validates the arguments of an init call and fills the handle; launches nothing
+int fill_ctx(pgxgo_ctx* h, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts, void* state_dev, size_t state_bytes) {
+  if (batch <= 0 || (board_size != 9 && board_size != 19) || !state_dev) return PGXGO_EINVAL;
+  if (((uintptr_t)state_dev & 255u) != 0) return PGXGO_EINVAL;
+  const int P = board_size * board_size;
+  pgxgo_opts o;
+  if (opts) o = *opts;
+  else { o.komi_x2 = 15; o.max_steps = 0; o.auto_reset = 0; o.obs_pitch = 0; o.mask_pitch = 0; o.stream = nullptr; }
+  if (o.max_steps == 0) o.max_steps = 2 * P;
+  if (o.max_steps < 1 || o.max_steps > 65535) return PGXGO_EINVAL;
+  if (o.obs_pitch == 0) o.obs_pitch = P * 17;
+  if (o.mask_pitch == 0) o.mask_pitch = P + 1;
+  if (o.obs_pitch < P * 17 || o.mask_pitch < P + 1) return PGXGO_EINVAL;
+  size_t off_meta, off_rew, off_term;
+  const size_t need = board_size == 19 ? state_bytes_for<19>(batch, &off_meta, &off_rew, &off_term)
+                                       : state_bytes_for<9>(batch, &off_meta, &off_rew, &off_term);
+  if (state_bytes < need) return PGXGO_EINVAL;
+  *h = pgxgo_ctx{};
+  h->B = batch; h->N = board_size; h->seed = seed;
+  h->wb = board_size == 19 ? auto_boards_per_wavefront<19>(batch) : auto_boards_per_wavefront<9>(batch);
+  h->komi_x2 = o.komi_x2; h->max_steps = o.max_steps; h->auto_reset = o.auto_reset ? 1 : 0;
+  h->obs_pitch = o.obs_pitch; h->mask_pitch = o.mask_pitch;
+  h->stream = (hipStream_t)o.stream;
+  uint8_t* base = (uint8_t*)state_dev;
+  h->planes = (uint4*)base;
+  h->meta = (uint4*)(base + off_meta);
+  h->rew_int = (float*)(base + off_rew);
+  h->term_int = base + off_term;
+  h->mask_out = nullptr; h->obs_out = nullptr; h->rew_out = h->rew_int; h->term_out = h->term_int;
+  return PGXGO_OK;
+}
+
+// State of the handle made by pgxgo_init_static (callers that cannot allocate device memory).  In host code the
+// array's name is only a stand-in: its device address comes from hipGetSymbolAddress, once per device.
+constexpr int kMaxStaticDevices = 16;
+void* g_scratch_ptr[kMaxStaticDevices] = {};
+pgxgo_ctx g_static_ctx[kMaxStaticDevices] = {};
+
 }  // namespace
+
+static __device__ __align__(256) unsigned char scratch[PGXGO_STATIC_STATE_BYTES];
 
 extern "C" {
 
@@ -1755,35 +1795,11 @@ int32_t pgxgo_obs_bytes(int32_t n) { return (n == 19 || n == 9) ? n * n * 17 : 0
 int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts, void* state_dev, size_t state_bytes) {
   if (!out) return PGXGO_EINVAL;
   *out = nullptr;
-  if (batch <= 0 || (board_size != 9 && board_size != 19) || !state_dev) return PGXGO_EINVAL;
-  if (((uintptr_t)state_dev & 255u) != 0) return PGXGO_EINVAL;
-  const int P = board_size * board_size;
-  pgxgo_opts o;
-  if (opts) o = *opts;
-  else { o.komi_x2 = 15; o.max_steps = 0; o.auto_reset = 0; o.obs_pitch = 0; o.mask_pitch = 0; o.stream = nullptr; }
-  if (o.max_steps == 0) o.max_steps = 2 * P;
-  if (o.max_steps < 1 || o.max_steps > 65535) return PGXGO_EINVAL;
-  if (o.obs_pitch == 0) o.obs_pitch = P * 17;
-  if (o.mask_pitch == 0) o.mask_pitch = P + 1;
-  if (o.obs_pitch < P * 17 || o.mask_pitch < P + 1) return PGXGO_EINVAL;
-  size_t off_meta, off_rew, off_term;
-  const size_t need = board_size == 19 ? state_bytes_for<19>(batch, &off_meta, &off_rew, &off_term)
-                                       : state_bytes_for<9>(batch, &off_meta, &off_rew, &off_term);
-  if (state_bytes < need) return PGXGO_EINVAL;
+  if (!state_dev) return PGXGO_EINVAL;
   pgxgo_ctx* h = (pgxgo_ctx*)calloc(1, sizeof(pgxgo_ctx));
   if (!h) return PGXGO_ENOMEM;
-  h->B = batch; h->N = board_size; h->seed = seed;
-  h->wb = board_size == 19 ? auto_boards_per_wavefront<19>(batch) : auto_boards_per_wavefront<9>(batch);
-  h->komi_x2 = o.komi_x2; h->max_steps = o.max_steps; h->auto_reset = o.auto_reset ? 1 : 0;
-  h->obs_pitch = o.obs_pitch; h->mask_pitch = o.mask_pitch;
-  h->stream = (hipStream_t)o.stream;
-  uint8_t* base = (uint8_t*)state_dev;
-  h->planes = (uint4*)base;
-  h->meta = (uint4*)(base + off_meta);
-  h->rew_int = (float*)(base + off_rew);
-  h->term_int = base + off_term;
-  h->mask_out = nullptr; h->obs_out = nullptr; h->rew_out = h->rew_int; h->term_out = h->term_int;
-  int rc = DISPATCH_N(h, launch_reset<19>(h, 1), launch_reset<9>(h, 1));
+  int rc = fill_ctx(h, batch, board_size, seed, opts, state_dev, state_bytes);
+  if (rc == PGXGO_OK) rc = DISPATCH_N(h, launch_reset<19>(h, 1), launch_reset<9>(h, 1));
   if (rc == PGXGO_OK) {
     hipError_t e = hipStreamSynchronize(h->stream);
     if (e != hipSuccess) { g_last_hip = (int)e; rc = PGXGO_EHIP; }
@@ -1793,8 +1809,34 @@ int pgxgo_init(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, c
   return PGXGO_OK;
 }
 
+int pgxgo_init_static(pgxgo_t* out, int32_t batch, int32_t board_size, uint32_t seed, const pgxgo_opts* opts) {
+  if (!out) return PGXGO_EINVAL;
+  *out = nullptr;
+  int dev = -1;
+  HIPCHK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxStaticDevices) return PGXGO_EINVAL;
+  if (!g_scratch_ptr[dev]) {   // once per device, with that device current: each GPU holds its own copy of the array
+    void* ptr = nullptr;
+    HIPCHK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr || ((uintptr_t)ptr & 255u) != 0) return PGXGO_EINVAL;
+    g_scratch_ptr[dev] = ptr;
+  }
+  if (batch <= 0 || (board_size != 9 && board_size != 19)) return PGXGO_EINVAL;
+  const size_t need = board_size == 19 ? state_bytes_for<19>(batch, nullptr, nullptr, nullptr) : state_bytes_for<9>(batch, nullptr, nullptr, nullptr);
+  if (need > (size_t)PGXGO_STATIC_STATE_BYTES) return PGXGO_ELIMIT;
+  pgxgo_ctx* h = &g_static_ctx[dev];
+  const int rc = fill_ctx(h, batch, board_size, seed, opts, g_scratch_ptr[dev], (size_t)PGXGO_STATIC_STATE_BYTES);
+  if (rc != PGXGO_OK) return rc;
+  // everything the handle reads is (re)written by this launch: rows, scalars, rewards, terminated flags of `batch` games
+  const int rc2 = DISPATCH_N(h, launch_reset<19>(h, 1), launch_reset<9>(h, 1));
+  if (rc2 != PGXGO_OK) return rc2;
+  *out = h;
+  return PGXGO_OK;
+}
+
 int pgxgo_destroy(pgxgo_t h) {
   if (!h) return PGXGO_EINVAL;
+  if (h >= g_static_ctx && h < g_static_ctx + kMaxStaticDevices) return PGXGO_OK;   // a static handle owns no host memory
   free(h);
   return PGXGO_OK;
 }
@@ -1987,6 +2029,7 @@ const char* pgxgo_strerror(int code) {
     case PGXGO_EINVAL: return "invalid argument";
     case PGXGO_EHIP: return "HIP runtime error";
     case PGXGO_ENOMEM: return "out of host memory";
+    case PGXGO_ELIMIT: return "size beyond the limit of the library's static buffer";
     default: return "unknown error";
   }
 }
