@@ -37,6 +37,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "pgxgo.h"
 #include "wave_common.hpp"
 
@@ -248,9 +250,9 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
 
 // Legal mask bytes [N*N+1] of every board of the wavefront.  With the tight pitch the boards of a wavefront are
 // one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
-template <int N, bool TIGHT>
+template <int N, bool TIGHT, bool NT = false>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
-                                          uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
+                                          uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
   static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
   constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1
@@ -270,19 +272,19 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::A / 16 + 63) / 64>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane, nt);
+    emit_bytes<(G::W * G::A / 16 + 63) / 64, NT>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::MASK_ROUNDS>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane, nt);
+      if (jj < nb) emit_bytes<G::MASK_ROUNDS, NT>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
   }
   wave_lds_fence();
 }
 
 // Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
-template <int N, bool TIGHT>
+template <int N, bool TIGHT, bool NT = false>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
-                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
+                                         int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
   static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
   constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17
@@ -334,11 +336,11 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::OBS / 16 + 63) / 64>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane, nt);
+    emit_bytes<(G::W * G::OBS / 16 + 63) / 64, NT>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::OBS_ROUNDS>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane, nt);
+      if (jj < nb) emit_bytes<G::OBS_ROUNDS, NT>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
   }
   wave_lds_fence();
 }
@@ -346,9 +348,9 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
 template <int N, bool TIGHT>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
-                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W, bool nt = false) {
-  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb, nt);
-  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb, nt);
+                                             uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
+  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
+  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -631,13 +633,13 @@ struct StepArgs {
   int32_t* next_actions;
 };
 
-template <int N, bool SAMPLE, bool TIGHT>
+template <int N, bool SAMPLE, bool TIGHT, bool NT>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
-  const int wib = threadIdx.x >> 6;
+  const int wib = wave_in_block();
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);   // in a wavefront beyond the batch no lane is valid
   const size_t rows_total = (size_t)a.B * N;
@@ -669,9 +671,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   }
 
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
+  if (a.obs) emit_obs<N, TIGHT, NT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb, a.nt_store != 0);
+  if (a.mask) emit_mask<N, TIGHT, NT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
@@ -986,7 +988,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
-  const int wib = threadIdx.x >> 6;
+  const int wib = wave_in_block();
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
   const size_t rows_total = (size_t)a.B * N;
@@ -1046,9 +1048,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel
   if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
   sk_clear_tables<N>(L, do_reset, zt, zcur, L.b);
 
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
+  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb, a.nt_store != 0);
+  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
   if (!skip) {
     if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
     else store_row<N>(a.planes, rows_total, L, R);
@@ -1139,7 +1141,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
-  const int wib = threadIdx.x >> 6;
+  const int wib = wave_in_block();
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   Lane<N> L(wave, threadIdx.x & 63, a.n);
   const size_t rows_total = (size_t)a.pool * N;
@@ -1253,7 +1255,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
   fill_spread_table(lut);
-  const int wib = threadIdx.x >> 6;
+  const int wib = wave_in_block();
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   if (wave * a.wb >= a.B) return;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
@@ -1324,7 +1326,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
     emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
-                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb, a.nt_store != 0);
+                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
   }
@@ -1345,7 +1347,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
   fill_spread_table(lut);
-  const int wib = threadIdx.x >> 6;
+  const int wib = wave_in_block();
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   if (wave * G::W >= B) return;
   const Lane<N> L(wave, threadIdx.x & 63, B);
@@ -1372,7 +1374,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(
                                                                                 const uint4* zcur) {
   using G = Geo<N>;
   __shared__ uint32_t sk_scratch[SK ? kWavesPerBlock : 1][64];
-  const int wave = blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
+  const int wave = blockIdx.x * kWavesPerBlock + wave_in_block();
   if (wave * G::W >= B) return;
   const Lane<N> L(wave, threadIdx.x & 63, B);
   Row<N> R;
@@ -1397,7 +1399,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(
     SkWin none[3];
     none[0].home = none[1].home = none[2].home = ~0u;
     none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
-    legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, sk_scratch[threadIdx.x >> 6]);
+    legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, sk_scratch[wave_in_block()]);
   }
   const bool wait = L.boardok && start_t && (int64_t)t < (int64_t)start_t[L.b];
   const Draw<N> d = draw_action<N>(L, legal, seed, t, wait);
@@ -1655,10 +1657,16 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
     HIPCHK(hipGetLastError());
     return PGXGO_OK;
   }
-  if (sample && tight) hipLaunchKernelGGL((go_step_kernel<N, true, true>), grid, block, 0, h->stream, a);
-  else if (sample) hipLaunchKernelGGL((go_step_kernel<N, true, false>), grid, block, 0, h->stream, a);
-  else if (tight) hipLaunchKernelGGL((go_step_kernel<N, false, true>), grid, block, 0, h->stream, a);
-  else hipLaunchKernelGGL((go_step_kernel<N, false, false>), grid, block, 0, h->stream, a);
+  const bool nt = a.nt_store != 0;
+  auto go = [&](auto sample_c, auto tight_c) {
+    constexpr bool S = decltype(sample_c)::value, T = decltype(tight_c)::value;
+    if (nt) hipLaunchKernelGGL((go_step_kernel<N, S, T, true>), grid, block, 0, h->stream, a);
+    else hipLaunchKernelGGL((go_step_kernel<N, S, T, false>), grid, block, 0, h->stream, a);
+  };
+  if (sample && tight) go(std::true_type{}, std::true_type{});
+  else if (sample) go(std::true_type{}, std::false_type{});
+  else if (tight) go(std::false_type{}, std::true_type{});
+  else go(std::false_type{}, std::false_type{});
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }

@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   __shared__ uint2 lut[256];
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
-  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   const Lane L(wave, lane, a.B);
   const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
@@ -330,7 +330,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_kernel(Rollou
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
   fill_spread_table(lut);
-  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   if (wave * W >= a.B) return;
   const Lane L(wave, lane, a.B);
@@ -363,7 +363,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uin
   __shared__ uint2 lut[256];
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
-  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   const Lane L(wave, lane, B);
   const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uin
 
 __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_random_actions_kernel(const uint32_t* rows, const uint4* meta, int B, uint32_t seed, uint32_t t,
                                                                                 const int32_t* start_t, int32_t* actions) {
-  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
   const int wave = blockIdx.x * kWavesPerBlock + wib;
   if (wave * W >= B) return;
   const Lane L(wave, lane, B);

@@ -22,6 +22,10 @@ __device__ __forceinline__ uint32_t env_hash(uint32_t seed, uint32_t tag, uint32
   return mixer(mixer(mixer(seed + 0x9E3779B9u * (tag + 1u)) ^ env) ^ t);
 }
 
+// index of the calling wavefront within its block, as a value the compiler knows to be the same in every lane
+// (so that everything derived from it -- output addresses, trip counts -- is computed once per wavefront)
+__device__ __forceinline__ int wave_in_block() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // ------------------------------------------------------------------------------------------------
 // cross-lane primitives.  All of them must be called with every lane of the wavefront active.
 // ------------------------------------------------------------------------------------------------
@@ -59,10 +63,21 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
   __syncthreads();
 }
 
-// nt (the same for the whole wavefront): store the vectors with the non-temporal hint.  That pays only when a launch
-// writes far more than the memory-side cache holds; below that size it is slower.
-template <int ROUNDS>
-__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane, bool nt = false) {
+// NT: store the vectors with the non-temporal hint.  That pays only when a launch writes far more than the
+// memory-side cache holds; below that size it is slower.  dst and nbytes must be the same in every lane.
+template <bool NT>
+__device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
+  if constexpr (NT) {
+    typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
+    const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
+    __builtin_nontemporal_store(v4, (vec4u*)p);
+  } else {
+    *p = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  }
+}
+
+template <int ROUNDS, bool NT = false>
+__device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
   uint8_t* base = dst - head;
   const uint32_t total = head + nbytes;
@@ -71,25 +86,34 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   const uint16_t* src = (const uint16_t*)bits + mine;
   uint4* out = (uint4*)base + mine;
   constexpr int GROUP = 6;   // rounds in flight at a time (bounds the registers held by pending LDS reads)
+  // Rounds in which every lane has a group need no per-lane test; with a full wavefront of boards that is all but
+  // the last round, and the choice is the same for the whole wavefront.
+  const bool full_but_last = m1 >= m0 + 64u * (uint32_t)(ROUNDS - 1);
+  if (ROUNDS > 1 && full_but_last) {
 #pragma unroll
-  for (int g = 0; g < ROUNDS; g += GROUP) {
-    uint32_t v[GROUP];
+    for (int g = 0; g < ROUNDS - 1; g += GROUP) {
+      uint32_t v[GROUP];
 #pragma unroll
-    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = (mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+      for (int i = g; i < g + GROUP && i < ROUNDS - 1; ++i) v[i - g] = (uint32_t)src[64 * i];
 #pragma unroll
-    for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
-      const uint2 lo = lut[v[i - g] & 255u], hi = lut[v[i - g] >> 8];
-      if (mine + 64u * i < m1) {
-        if (nt) {
-          typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
-          const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
-          __builtin_nontemporal_store(v4, (vec4u*)&out[64 * i]);
-        } else {
-          out[64 * i] = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        }
-      }
+      for (int i = g; i < g + GROUP && i < ROUNDS - 1; ++i) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
+    if (mine + 64u * (ROUNDS - 1) < m1) {
+      const uint32_t v = (uint32_t)src[64 * (ROUNDS - 1)];
+      store16<NT>(&out[64 * (ROUNDS - 1)], lut[v & 255u], lut[v >> 8]);
+    }
+  } else {
+#pragma unroll
+    for (int g = 0; g < ROUNDS; g += GROUP) {
+      uint32_t v[GROUP];
+#pragma unroll
+      for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = (mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+#pragma unroll
+      for (int i = g; i < g + GROUP && i < ROUNDS; ++i)
+        if (mine + 64u * i < m1) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
   if (lane < 32) {
     uint32_t i = lane & 15u, pos;
