@@ -322,14 +322,21 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
     uint32_t head;
     if constexpr (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * G::OBS) & 15u) + (uint32_t)(L.j * G::OBS); reg = lds_obs; }
     else { head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u); reg = lds_obs + L.j * G::OBS_DW; }
-    const uint32_t o = head + (uint32_t)(G::ROWBITS * L.r), q = o >> 5, s = o & 31u;
-    reg += q;
-    // shifted string T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door
-    atomicOr(&reg[0], S[0] << s);
+    // The row's string goes to bit offset o of the stream.  Written as a left shift by u = 1..32 from dword (o-u)/32
+    // on, every shifted dword is one funnel shift of two neighbours of S (a shift by 0 would need a special case):
+    // T[i] = bits of dword q+i; T[0] and T[NI+1..NR] may share their dword with the rows next door.
+    const uint32_t o = head + (uint32_t)(G::ROWBITS * L.r);
+    const uint32_t u1 = (o + 31u) & 31u;            // u - 1
+    reg += (int32_t)(o - 1u - u1) >> 5;             // dword -1 only when o = 0, and then T[0] = 0 is not written
+    const uint32_t sh = 31u - u1;                   // right shift of the (S[i], S[i-1]) pair that equals the left shift by u
+    {
+      const uint32_t t0 = __builtin_amdgcn_alignbit(S[0], 0u, sh);
+      if (t0) atomicOr(&reg[0], t0);
+    }
 #pragma unroll
     for (int i = 1; i <= G::NR; ++i) {
-      uint32_t hi = (i < G::NR) ? S[i] : 0u;
-      uint32_t t = __funnelshift_l(S[i - 1], hi, s);
+      const uint32_t hi = (i < G::NR) ? S[i] : 0u;
+      const uint32_t t = __builtin_amdgcn_alignbit(hi, S[i - 1], sh);
       if (i <= G::NI) reg[i] = t;
       else if (t) atomicOr(&reg[i], t);
     }
