@@ -307,6 +307,239 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Board-per-lane mapping for very large batches: a lane holds a whole board as two 121-bit sets (cell p = 11*row + col
+// is bit p of four dwords), a wavefront 64 boards.  Everything that the row-per-lane mapping pays once per 5 boards
+// (decode, hash, draw, scalars, emission set-up) is paid once per 64; the flood runs until the slowest of the 64 boards
+// has converged.  Same state layout, same outputs, same results; chosen by the launch code above a batch threshold.
+// ------------------------------------------------------------------------------------------------
+struct B128 {
+  uint32_t w[4];
+};
+constexpr bool cell_in(int kind, int p) {   // 0: the board, 1: column 0, 2: column 10, 3: row 0, 4: row 10
+  return kind == 0 ? true : kind == 1 ? p % N == 0 : kind == 2 ? p % N == N - 1 : kind == 3 ? p / N == 0 : p / N == N - 1;
+}
+constexpr uint32_t set_word(int kind, int i) {
+  uint32_t v = 0u;
+  for (int p = 32 * i; p < 32 * i + 32 && p < P; ++p)
+    if (cell_in(kind, p)) v |= 1u << (p - 32 * i);
+  return v;
+}
+template <int KIND>
+__device__ __forceinline__ B128 set_of() { return B128{{set_word(KIND, 0), set_word(KIND, 1), set_word(KIND, 2), set_word(KIND, 3)}}; }
+
+__device__ __forceinline__ B128 b_or(B128 a, B128 b) { return B128{{a.w[0] | b.w[0], a.w[1] | b.w[1], a.w[2] | b.w[2], a.w[3] | b.w[3]}}; }
+__device__ __forceinline__ B128 b_and(B128 a, B128 b) { return B128{{a.w[0] & b.w[0], a.w[1] & b.w[1], a.w[2] & b.w[2], a.w[3] & b.w[3]}}; }
+__device__ __forceinline__ B128 b_andn(B128 a, B128 b) { return B128{{a.w[0] & ~b.w[0], a.w[1] & ~b.w[1], a.w[2] & ~b.w[2], a.w[3] & ~b.w[3]}}; }
+__device__ __forceinline__ bool b_any(B128 a) { return (a.w[0] | a.w[1] | a.w[2] | a.w[3]) != 0u; }
+__device__ __forceinline__ bool b_ne(B128 a, B128 b) { return ((a.w[0] ^ b.w[0]) | (a.w[1] ^ b.w[1]) | (a.w[2] ^ b.w[2]) | (a.w[3] ^ b.w[3])) != 0u; }
+__device__ __forceinline__ B128 b_bit(int p, bool on) {   // the set {p} (empty when !on)
+  const uint32_t bit = on ? 1u << (p & 31) : 0u;
+  const int i = p >> 5;
+  return B128{{i == 0 ? bit : 0u, i == 1 ? bit : 0u, i == 2 ? bit : 0u, i == 3 ? bit : 0u}};
+}
+template <int K>
+__device__ __forceinline__ B128 b_up(B128 x) {     // cell p -> p + K
+  return B128{{x.w[0] << K, __builtin_amdgcn_alignbit(x.w[1], x.w[0], 32 - K), __builtin_amdgcn_alignbit(x.w[2], x.w[1], 32 - K),
+               __builtin_amdgcn_alignbit(x.w[3], x.w[2], 32 - K)}};
+}
+template <int K>
+__device__ __forceinline__ B128 b_down(B128 x) {   // cell p -> p - K
+  return B128{{__builtin_amdgcn_alignbit(x.w[1], x.w[0], K), __builtin_amdgcn_alignbit(x.w[2], x.w[1], K), __builtin_amdgcn_alignbit(x.w[3], x.w[2], K),
+               x.w[3] >> K}};
+}
+// all cells touching the set x (the same six neighbours as hex_dilate); bits beyond cell 120 may be set
+__device__ __forceinline__ B128 dilate128(B128 x) {
+  const B128 not_last = b_andn(x, set_of<2>()), not_first = b_andn(x, set_of<1>());
+  return b_or(b_or(b_or(b_up<1>(not_last), b_down<N - 1>(not_last)), b_or(b_down<1>(not_first), b_up<N - 1>(not_first))), b_or(b_down<N>(x), b_up<N>(x)));
+}
+
+// bit i of x (x < 256) -> bit 4i, from a table in LDS
+__device__ __forceinline__ void fill_spread4_table(uint32_t* lut4) {
+  for (uint32_t x = threadIdx.x; x < 256u; x += blockDim.x) lut4[x] = spread_every4(x);
+}
+
+// Puts the ND-dword bit string S at bit offset o of an LDS bit stream: a left shift by 1..32 from dword (o-1)/32 on, so
+// that every stream dword is one funnel shift of two neighbours of S.  Stream dwords OWN_LO..OWN_HI (relative to the
+// first) hold bits of this string only whatever o is and are stored plainly; the others are OR-ed in.
+template <int ND, int OWN_LO, int OWN_HI>
+__device__ __forceinline__ void stream_put(uint32_t* stream, const uint32_t (&S)[ND], uint32_t o) {
+  const uint32_t u1 = (o + 31u) & 31u;
+  uint32_t* reg = stream + ((int32_t)(o - 1u - u1) >> 5);   // dword -1 only when o = 0, and then nothing is written there
+  const uint32_t sh = 31u - u1;
+  const uint32_t t0 = __builtin_amdgcn_alignbit(S[0], 0u, sh);
+  if (t0) atomicOr(&reg[0], t0);
+#pragma unroll
+  for (int i = 1; i <= ND; ++i) {
+    const uint32_t t = __builtin_amdgcn_alignbit(i < ND ? S[i] : 0u, S[i - 1], sh);
+    if (i >= OWN_LO && i <= OWN_HI) reg[i] = t;
+    else if (t) atomicOr(&reg[i], t);
+  }
+}
+
+constexpr int LANE_MASK_DW = ((15 + 64 * A + 31) / 32 + 3) / 4 * 4;   // LDS dwords of a wavefront's streams: 64 boards
+constexpr int LANE_OBS_DW = ((15 + 64 * OBS + 31) / 32 + 3) / 4 * 4;
+constexpr int LANE_MASK_ROUNDS = (64 * A / 16 + 63) / 64;
+constexpr int LANE_OBS_ROUNDS = (64 * OBS / 16 + 63) / 64;
+
+template <bool SAMPLE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(StepArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ uint32_t lut4[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][LANE_OBS_DW];
+  __shared__ __align__(16) uint32_t lds_mask[kWavesPerBlock][LANE_MASK_DW];
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int b0 = wave * 64;                 // first board of the wavefront
+  const int b = b0 + lane;
+  const bool ok = b < a.B;
+  // state: 11 row words (black bits 0-10, white bits 16-26), the scalar record, the action
+  uint32_t row[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) row[r] = ok ? a.rows[(size_t)b * N + r] : 0u;
+  const uint4 mv = ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u);
+  const int act = ok ? a.actions[b] : -1;
+  fill_spread4_table(lut4);
+  fill_spread_table(lut);                   // ends with the block's only barrier
+  if (b0 >= a.B) return;
+  const int nb = a.B - b0 < 64 ? a.B - b0 : 64;
+  Meta m = unpack_meta(mv);
+
+  B128 bk = {{0u, 0u, 0u, 0u}}, wt = {{0u, 0u, 0u, 0u}};
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    const int i = (N * r) >> 5, s = (N * r) & 31;
+    const uint32_t kb = row[r] & FULL, kw = (row[r] >> 16) & FULL;
+    bk.w[i] |= kb << s; wt.w[i] |= kw << s;
+    if (s + N > 32) { bk.w[i + 1] |= kb >> (32 - s); wt.w[i + 1] |= kw >> (32 - s); }
+  }
+
+  // ---- a1-a5: decode, legality gate, placement or swap, winner test, rewards / termination / auto-reset -------------
+  const bool skip = act == -1 || !ok;
+  const bool frozen = !skip && m.term;
+  const bool live = !skip && !frozen;
+  const B128 board = set_of<0>();
+  const B128 E0 = b_andn(board, b_or(bk, wt));
+  const bool want_point = live && act >= 0 && act < P;
+  const B128 pbit = b_bit(want_point ? act : 0, want_point);
+  const bool point_ok = want_point && b_any(b_and(E0, pbit));
+  const bool swap_ok = live && act == P && m.steps == 1;
+  const bool illegal_now = live && !point_ok && !swap_ok;
+  const bool moved = point_ok || swap_ok;
+  const int wtm = m.wtm;
+  B128 placed = pbit;
+  if (!point_ok) placed = B128{{0u, 0u, 0u, 0u}};
+  if (swap_ok) {   // Black's lone stone (r0,c0) comes off, a white stone goes to (c0,r0); once per game at most
+    const int p0 = bk.w[0] ? __ffs(bk.w[0]) - 1 : bk.w[1] ? 31 + __ffs(bk.w[1]) : bk.w[2] ? 63 + __ffs(bk.w[2]) : 95 + __ffs(bk.w[3]);
+    const int r0 = p0 / N, c0 = p0 - r0 * N;
+    placed = b_bit(c0 * N + r0, true);
+    bk = B128{{0u, 0u, 0u, 0u}}; wt = placed;
+  } else if (wtm) {
+    wt = b_or(wt, placed);
+  } else {
+    bk = b_or(bk, placed);
+  }
+  // winner test: the chain of the new stone must touch both of the mover's sides
+  const B128 S = wtm ? wt : bk;
+  B128 F = placed;
+  for (;;) {
+    F = b_or(F, b_and(dilate128(F), S));
+    const B128 G = b_or(F, b_and(dilate128(F), S));
+    const bool ch = b_ne(G, F);
+    F = G;
+    if (__ballot(ch) == 0ull) break;
+  }
+  const bool hit_a = b_any(b_and(F, wtm ? set_of<1>() : set_of<3>()));
+  const bool hit_b = b_any(b_and(F, wtm ? set_of<2>() : set_of<4>()));
+  const bool won = moved && hit_a && hit_b;
+
+  const int mover = wtm ? 1 - m.bp : m.bp;
+  m.steps += moved ? 1 : 0;
+  m.wtm = wtm ^ (moved ? 1 : 0);
+  const bool ended = illegal_now || won;
+  const float r_mover = won ? 1.f : (illegal_now ? -1.f : 0.f);
+  const float r_other = won ? -1.f : (illegal_now ? 1.f : 0.f);
+  m.illegal += illegal_now ? 1u : 0u;
+  m.term = (m.term || ended) ? 1 : 0;
+  const bool reset = ended && a.auto_reset;
+  if (reset) {   // Sec. 4.1: back to the initial state within the same ply
+    m.episode += 1u;
+    bk = B128{{0u, 0u, 0u, 0u}}; wt = bk;
+    m.steps = 0; m.wtm = 0; m.term = 0;
+    m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)b, m.episode) & 1u);
+  }
+  if (!skip) {
+    *(float2*)(a.rew + 2 * (size_t)b) = mover == 0 ? make_float2(r_mover, r_other) : make_float2(r_other, r_mover);
+    a.term[b] = (ended || frozen) ? 1 : 0;
+    a.meta[b] = pack_meta(m);
+    // a8: state store.  A placed stone changes one bit of one row word; a swap or a reset rewrites the board.
+    if (swap_ok || reset) {
+#pragma unroll
+      for (int r = 0; r < N; ++r) {
+        const int i = (N * r) >> 5, s = (N * r) & 31;
+        uint32_t kb = bk.w[i] >> s, kw = wt.w[i] >> s;
+        if (s + N > 32) { kb |= bk.w[i + 1] << (32 - s); kw |= wt.w[i + 1] << (32 - s); }
+        a.rows[(size_t)b * N + r] = (kb & FULL) | ((kw & FULL) << 16);
+      }
+    } else if (point_ok) {
+      const int pr = (int)(__umul24((uint32_t)act, 745u) >> 13);   // act / 11 for 0 <= act < 128
+      atomicOr(&a.rows[(size_t)b * N + pr], (1u << (act - pr * N)) << (wtm ? 16 : 0));
+    }
+  }
+
+  // ---- a6 / a7: legal mask [122] and observation [11][11][4] of the position after the ply ------------------------------
+  const bool swap = m.steps == 1;
+  B128 legal = b_andn(board, b_or(bk, wt));
+  if (swap) legal.w[3] |= 1u << (P - 96);   // the swap is action 121, the last one
+  {
+    uint4* z = (uint4*)lds_obs[wib];
+#pragma unroll
+    for (int i = 0; i < (LANE_OBS_DW / 4 + 63) / 64; ++i)
+      if (i * 64 + lane < LANE_OBS_DW / 4) z[i * 64 + lane] = make_uint4(0u, 0u, 0u, 0u);
+    if (lane < LANE_MASK_DW / 4) ((uint4*)lds_mask[wib])[lane] = make_uint4(0u, 0u, 0u, 0u);
+    static_assert(LANE_MASK_DW / 4 <= 64, "the mask stream is cleared by one store per lane");
+  }
+  wave_lds_fence();
+  if (a.mask && ok) {
+    const uint32_t head = (uint32_t)((uintptr_t)(a.mask + (size_t)b0 * A) & 15u);
+    stream_put<4, 1, 2>(lds_mask[wib], legal.w, head + (uint32_t)(A * lane));
+  }
+  if (a.obs && ok) {
+    // 4 bits per cell: mover's stone, opponent's stone, Black to move, swap legal
+    const B128 mine = m.wtm ? wt : bk, theirs = m.wtm ? bk : wt;
+    const uint32_t flags = (m.wtm ? 0u : 0x44444444u) | (swap ? 0x88888888u : 0u);
+    uint32_t O[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      const uint32_t mb = (mine.w[k >> 2] >> (8 * (k & 3))) & 255u, tb = (theirs.w[k >> 2] >> (8 * (k & 3))) & 255u;
+      O[k] = lut4[mb] | (lut4[tb] << 1) | (k < 15 ? flags : (flags & 0xFu));
+    }
+    const uint32_t head = (uint32_t)((uintptr_t)(a.obs + (size_t)b0 * OBS) & 15u);
+    stream_put<16, 1, 14>(lds_obs[wib], O, head + (uint32_t)(OBS * lane));
+  }
+  wave_lds_fence();
+  if (a.mask) emit_bytes<LANE_MASK_ROUNDS>(lds_mask[wib], lut, a.mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
+  if (a.obs) emit_bytes<LANE_OBS_ROUNDS>(lds_obs[wib], lut, a.obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
+
+  if (SAMPLE) {   // the next uniform random legal action: the k-th set bit of the legal set, k = hash mod count
+    const bool wait = a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
+    const uint32_t c0 = __popc(legal.w[0]), c1 = __popc(legal.w[1]), c2 = __popc(legal.w[2]), c3 = __popc(legal.w[3]);
+    const uint32_t total = c0 + c1 + c2 + c3;
+    uint32_t k = env_hash(a.sample_seed, 0u, (uint32_t)b, a.sample_t) % (total ? total : 1u);
+    uint32_t w = legal.w[0], base = 0u;
+    if (k >= c0) { k -= c0; w = legal.w[1]; base = 32u;
+      if (k >= c1) { k -= c1; w = legal.w[2]; base = 64u;
+        if (k >= c2) { k -= c2; w = legal.w[3]; base = 96u; } } }
+    uint32_t pos = 0u;
+#pragma unroll
+    for (int width = 16; width >= 1; width >>= 1) {
+      const uint32_t c = __popc(w & ((1u << width) - 1u));
+      if (k >= c) { k -= c; w >>= width; pos += width; }
+    }
+    if (ok) a.next_actions[b] = wait ? -1 : (total == 0u ? 0 : (int)(base + pos));
+  }
+}
+
 // `steps` plies of uniform random legal play in one launch (Sec. 2: all-on-device loops; Sec. 4.1: random policy with
 // auto-reset).  The state stays in registers; the outputs of ply i go to slice (i mod slices) of the caller's buffers.
 struct RolloutArgs {
@@ -480,9 +713,15 @@ struct pgxhex_ctx {
   uint8_t* obs_out;
   float* rew_out;
   uint8_t* term_out;
+  int mapping;   // 0: automatic, 1: a board row per lane, 2: a board per lane
 };
 
 namespace {
+
+// From this many games on the one-launch-per-ply kernel holds a board per lane (four or more 64-board wavefronts per
+// SIMD exist then); below, a board row per lane, which needs far fewer games to fill the machine.
+constexpr int kLaneMappingFrom = 196608;
+bool board_per_lane(const pgxhex_ctx* h) { return h->mapping == 2 || (h->mapping == 0 && h->B >= kLaneMappingFrom); }
 
 unsigned blocks_for(int B) {
   const unsigned waves = (unsigned)((B + W - 1) / W);
@@ -507,7 +746,11 @@ int launch_step(pgxhex_ctx* h, const int32_t* actions, bool sample, uint32_t see
   a.rows = h->rows; a.meta = h->meta; a.actions = actions; a.rew = h->rew_out; a.term = h->term_out; a.mask = h->mask_out; a.obs = h->obs_out;
   a.B = h->B; a.seed = h->seed; a.auto_reset = h->auto_reset;
   a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
-  if (sample) hipLaunchKernelGGL(hex_step_kernel<true>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  if (board_per_lane(h)) {
+    const dim3 grid((unsigned)((h->B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock)));
+    if (sample) hipLaunchKernelGGL(hex_step_lane_kernel<true>, grid, dim3(64 * kWavesPerBlock), 0, h->stream, a);
+    else hipLaunchKernelGGL(hex_step_lane_kernel<false>, grid, dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  } else if (sample) hipLaunchKernelGGL(hex_step_kernel<true>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   else hipLaunchKernelGGL(hex_step_kernel<false>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXHEX_OK;
@@ -660,6 +903,12 @@ int pgxhex_import_state(pgxhex_t h, const int8_t* board_dev, const int8_t* to_pl
   HIPCHK(hipGetLastError());
   if (h->mask_out || h->obs_out) return launch_emit(h, h->mask_out, h->obs_out);
   return PGXHEX_OK;
+}
+
+int pgxhex_set_mapping(pgxhex_t h, int32_t mapping) {
+  if (!h || mapping < 0 || mapping > 2) return PGXHEX_EINVAL;
+  h->mapping = mapping;
+  return board_per_lane(h) ? 2 : 1;
 }
 
 int pgxhex_sync(pgxhex_t h) {

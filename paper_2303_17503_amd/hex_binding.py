@@ -35,6 +35,7 @@ def lib():
         L.pgxhex_export_state.argtypes = [vp] * 8
         L.pgxhex_import_state.argtypes = [vp] * 7
         L.pgxhex_sync.argtypes = [vp]
+        L.pgxhex_set_mapping.argtypes = [vp, i32]
         L.pgxhex_boards_per_wavefront.restype = i32
         L.pgxhex_boards_per_wavefront.argtypes = []
         L.pgxhex_strerror.restype = C.c_char_p
@@ -98,6 +99,13 @@ class HexEnv:
         if terminated is not None: _need(terminated, torch.uint8, (self.B,), "terminated")
         _check(lib().pgxhex_set_output_buffers(self._h, _ptr(mask), _ptr(obs), _ptr(rewards), _ptr(terminated)), "pgxhex_set_output_buffers")
         self.mask_out, self.obs_out, self.rewards_out, self.terminated_out = mask, obs, rewards, terminated
+
+    def set_mapping(self, mapping=0):
+        """Launch shape of the step kernels: 1 = a board row per lane, 2 = a board per lane, 0 = automatic; returns the one in use."""
+        rc = lib().pgxhex_set_mapping(self._h, int(mapping))
+        if rc <= 0:
+            _check(rc if rc < 0 else -1, "pgxhex_set_mapping")
+        return rc
 
     def reset(self):
         _check(lib().pgxhex_reset(self._h), "pgxhex_reset")

@@ -24,9 +24,9 @@ sys.path.insert(0, ROOT)
 
 
 class Args:
-    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0, seed=None):
+    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0, seed=None, mapping=0):
         self.game, self.config, self.plies, self.threads, self.state_every = game, config, plies, threads, state_every
-        self.superko, self.rollout, self.seed = superko, rollout, seed
+        self.superko, self.rollout, self.seed, self.mapping = superko, rollout, seed, mapping
 
 
 def main():
@@ -40,9 +40,10 @@ def main():
                                                             "2: honoured by the legal mask)")
     ap.add_argument("--rollout", type=int, default=0, help="L > 0: use the rollout kernel, L plies per launch, every ply recorded in its own slice")
     ap.add_argument("--seed", type=int, default=None, help="another seed than the configuration's (more trajectories of the same shape)")
+    ap.add_argument("--mapping", type=int, default=0, help="Hex only: 1 = a board row per lane, 2 = a board per lane, 0 = the library's choice")
     a = ap.parse_args()
     try:
-        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout, a.seed))
+        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout, a.seed, a.mapping))
     except AssertionError as e:
         print(e, flush=True)
         sys.exit(1)
@@ -69,6 +70,9 @@ def run(args):
     st_dev = None if start is None else torch.as_tensor(start, device="cuda")
 
     env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset) if go else pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
+    if args.mapping:
+        assert not go, "the mapping is a Hex launch-shape choice"
+        assert env.set_mapping(args.mapping) == args.mapping
     if args.superko:
         assert go, "the superko rule is a Go option"
         env.enable_superko(int(args.superko))

@@ -26,6 +26,14 @@ def test_every_environment_every_ply(game, config):
         assert n > 65536 * 500          # configuration 4: 500 measured plies plus each game's own warm-up
 
 
+@pytest.mark.parametrize("config,mapping", [(1, 2), (2, 1)])
+def test_every_environment_every_ply_hex_in_the_other_mapping(config, mapping):
+    """The largest Hex workload is stepped with a board per lane and the others with a board row per lane by default;
+    here the other way round: 16384 games with a board per lane, 262144 with a board row per lane."""
+    n = full_parity.run(full_parity.Args(game="hex", config=config, mapping=mapping))
+    assert n == EXPECTED[("hex", config)]
+
+
 @pytest.mark.parametrize("config,mode", [(1, 1), (2, 1), (3, 1), (1, 2), (2, 2), (3, 2)])
 def test_every_environment_every_ply_with_superko(config, mode):
     """The same with the positional-superko rule on, enforced at play time (mode 1) and honoured by the legal mask (mode 2);

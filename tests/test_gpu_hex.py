@@ -15,11 +15,13 @@ def to_np(t):
 class HexPair:
     """A HexEnv on the GPU and a HexOracle on the CPU over the same environments (ids: a sample of them)."""
 
-    def __init__(self, batch, seed, auto_reset, ids=None, bind=True, mask=None, obs=None):
+    def __init__(self, batch, seed, auto_reset, ids=None, bind=True, mask=None, obs=None, mapping=0):
         import paper_2303_17503_amd as pg
         from oracle import hex as hx
         self.B = batch
         self.env = pg.HexEnv(batch, seed=seed, auto_reset=auto_reset)
+        if mapping:
+            assert self.env.set_mapping(mapping) == mapping       # 1: a board row per lane, 2: a board per lane
         self.ids = None if ids is None else np.asarray(ids, np.int32)
         self.orc = hx.HexOracle(batch if ids is None else len(ids), N, seed=seed, auto_reset=auto_reset, env_ids=self.ids)
         self.sel = None if ids is None else torch.as_tensor(self.ids.astype(np.int64), device="cuda")
@@ -131,6 +133,48 @@ def test_start_times_negative_zero_and_positive():
         q.orc.step(a)
         assert (got["mask"][t] == q.orc.legal_mask()).all(), f"mask t={t}"
     q.compare("state after the launch", last_step=False)
+
+
+@pytest.mark.parametrize("B", [1, 5, 63, 64, 65, 130, 333])
+@pytest.mark.parametrize("fused", [False, True])
+def test_board_per_lane_mapping(B, fused):
+    """The step kernels with a whole board per lane (the mapping used from ~200 k games on), forced at small ragged batches:
+    full wavefronts, partly filled ones, several blocks; random play with auto-reset and staggered starts, every ply compared."""
+    seed = 40 + B
+    start = ((np.arange(B) * 7) % 30 - 3).astype(np.int32)
+    p = HexPair(B, seed=seed, auto_reset=True, mapping=2)
+    p.rollout(seed, 0, 260, fused=fused, state_every=13, start_t=start)
+    assert to_np(p.env.export_state()["episode"]).max() >= 1
+    q = HexPair(B, seed=seed + 1, auto_reset=False, mapping=2)
+    q.rollout(seed + 1, 0, 125, fused=fused, state_every=25)
+    assert to_np(q.term).all()
+
+
+def test_board_per_lane_swap_illegal_frozen_and_skip():
+    B = 70
+    p = HexPair(B, seed=3, auto_reset=False, mapping=2)
+    first = (np.arange(B) * 5 + 2) % P
+    p.step(first)
+    p.compare("after the first stone")
+    assert to_np(p.mask)[:, P].all()
+    a = np.where(np.arange(B) % 2 == 0, P, (first + 1) % P)         # every other game swaps
+    p.step(a)
+    p.compare("after the swap")
+    bd = to_np(p.env.export_state()["board"]).reshape(B, N, N)
+    for b in range(0, B, 2):
+        r, c = divmod(int(first[b]), N)
+        assert bd[b, c, r] == -1 and np.abs(bd[b]).sum() == 1
+    kinds = np.arange(B) % 7
+    occupied = np.array([int(np.flatnonzero(bd[b].reshape(-1))[0]) for b in range(B)])
+    a = np.select([kinds == 0, kinds == 1, kinds == 2, kinds == 3, kinds == 4, kinds == 5], [occupied, 121, -7, 5000, -1, 122], default=60)
+    p.step(a)                                                       # occupied / swap off its turn / out of range x3 / skip / maybe legal
+    p.compare("illegal mix")
+    p.step(np.full(B, 61))                                          # finished games stay frozen
+    p.compare("frozen")
+    p.rollout(3, 4, 130)
+    for mapping in (1, 2):                                          # switching the mapping mid-game changes nothing
+        assert p.env.set_mapping(mapping) == mapping
+        p.rollout(3, 130, 140)
 
 
 def test_swap_rule():
