@@ -398,8 +398,8 @@ def bench_go(args, cfg):
     fill = fill_ceiling(out_bytes, S_rot)
     gap_us = launch_gap_us()
     copy_gbs = device_copy_gbs(out_bytes)
-    pmc_file = os.path.join("profiles", f"go_step_kernel_{cfg.name}_pmc.txt")
-    traffic = read_traffic(os.path.join(ROOT, pmc_file)) if with_obs and args.mode == "fused" and not args.superko else None
+    pmc_file = os.path.join("profiles", f"{'go_rollout_kernel' if args.mode == 'rollout' else 'go_step_kernel'}_{cfg.name}.txt")
+    traffic = read_traffic(os.path.join(ROOT, pmc_file)) if with_obs and args.mode != "separate" and not args.superko else None
     if dram is not None:
         a = bytes_ply * B / (dram["kernel_ms"] * 1e-3) / 1e9
         dram.update({"achieved": a, "frac": a / HBM_PEAK_GBS, "frac_of_fill": fill["rotating_ms"] / dram["kernel_ms"],
@@ -552,7 +552,7 @@ def bench_hex(args, cfg):
     if dram is not None:
         a = bytes_ply * B / (dram["kernel_ms"] * 1e-3) / 1e9
         dram.update({"achieved": a, "frac": a / HBM_PEAK_GBS, "frac_of_fill": fill["rotating_ms"] / dram["kernel_ms"]})
-    pmc_file = os.path.join("profiles", f"hex_step_kernel_{cfg.name}_pmc.txt")
+    pmc_file = os.path.join("profiles", f"{'hex_step_lane_kernel' if B >= 196608 else 'hex_step_kernel'}_{cfg.name}.txt")
     traffic = read_traffic(os.path.join(ROOT, pmc_file)) if with_obs and args.mode == "fused" else None
     out = {
         "metric": "Hex env steps/sec on 1 MI355X (11x11, random legal play); HBM GB/s % peak",
