@@ -703,50 +703,69 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
 // leaves such plays out; 1 = looked at only when the move is played (the offender loses like for any illegal
 // action) while the mask keeps showing the simple-ko set.
 //
-// Every position is summarised by a Zobrist key (XOR of one key per stone, updated from the stones that changed)
-// and its two stone counts.  A play by colour c always gives a position with exactly one more stone of colour c,
-// so the earlier positions a play can recreate are those whose count of c is (current count + 1): the per-game
-// table (open addressing, linear probing, 8-byte entries) holds every position twice, once on the probe chain of
-// (black, its black count) and once on that of (white, its white count).  Per ply that costs one chain look-up for
-// the played move, and one for the next mover's forbidden points, which is empty most of the time; only when an
-// earlier position with the right count exists is the set of plays that would recreate it worked out (the single
-// point whose key equals the key difference, or a capturing play whose captured chain has the right size and keys).
-// An entry = 45 key bits + both counts, so a false match needs equal counts and a 45-bit collision.
+// Every position is summarised by two 32-bit Zobrist keys, one per colour (XOR of one key per stone of that colour,
+// updated from the stones that changed), and its two stone counts.  A play by colour c always gives a position with
+// exactly one more stone of colour c, so the earlier positions a play can recreate are those whose count of c is
+// (current count + 1): the per-game table (open addressing, linear probing, 8-byte entries = the two keys) holds
+// every position twice, once on the probe chain of (black, its black count) and once on that of (white, its white
+// count).  Per ply that costs one chain walk to find where the new position goes and one for the next mover's
+// forbidden plays.  The latter needs no loop over the legal points: an earlier position q can be recreated by the
+// mover's play on p only if q's key of the mover's colour differs from the current one by exactly the key of a stone
+// on p, and the stone keys come from an invertible mixer, so every lane inverts the difference of the entry it holds
+// and sees at once whether it is a stone key at all (a random 32-bit value is one with probability 2^-22).  Only for
+// such an entry -- a genuine near-repetition -- is the rest checked: the other colour's keys must differ by nothing
+// (a play that takes nothing) or by exactly the keys of the chains the play takes.  The forbidden plays found when a
+// position arises are kept with the game (two points, or a marker to look again), so the next ply's legality gate
+// and the getters need no table access.
+// Equality of positions = equality of the 64 key bits; the empty board (keys 0,0 = an empty slot) is never stored
+// and can never be recreated.
 // ------------------------------------------------------------------------------------------------
 template <int N>
 struct Zt {
   static constexpr int LOG2 = N == 19 ? 11 : 9;
   static constexpr uint32_t SLOTS = 1u << LOG2;
   static constexpr uint32_t MASK = SLOTS - 1u;
+  static constexpr uint32_t WIN = N >= 16 ? 16u : 8u;   // slots a board's row lanes look at per round: one aligned 128- or 64-byte piece of the table
   static_assert(SLOTS > 2u * (2u * N * N + 9u), "two entries per position (ply cap + the imported history window) always leave empty slots");
 };
 
-__device__ __forceinline__ uint2 zkey(uint32_t point, uint32_t colour) {   // colour 0 black / 1 white
-  const uint32_t lo = mixer(0x9E3779B9u * (2u * point + colour + 1u));
-  return make_uint2(lo, mixer(lo + 0x85EBCA6Bu));
+// key of a stone: an invertible function of 2*point + colour + 1 (colour 0 black / 1 white)
+__device__ __forceinline__ uint32_t zkey(uint32_t point, uint32_t colour) { return mixer(0x9E3779B9u * (2u * point + colour + 1u)); }
+// 2*point + colour + 1 for a stone key, anything else for other values
+__device__ __forceinline__ uint32_t zkey_inverse(uint32_t x) {
+  x ^= x >> 16; x *= 0x43021123u;               // the mixer's steps undone in reverse order (odd multipliers are invertible mod 2^32)
+  x ^= (x >> 15) ^ (x >> 30); x *= 0x1d69e2a5u;
+  x ^= x >> 16;
+  return x * 0x144cbc89u;                        // 0x9E3779B9^-1
 }
 
-struct SkGame {   // key and stone counts of a game's current position (the same in every lane of the board)
+// Keys (x: black stones, y: white stones) and stone counts of a game's current position, and the plays that would
+// recreate an earlier position (fw: two points in 16 bits each, kNoPoint = none; kLookAgain in the low half = more than
+// two, to be found by walking the table again).  The same in every lane of the board.
+struct SkGame {
   uint2 key;
   int nb, nw;
+  uint32_t fw;
 };
+constexpr uint32_t kNoPoint = 0xFFFFu, kLookAgain = 0xFFFEu;
 __device__ __forceinline__ SkGame sk_unpack(uint4 v) {
   SkGame g;
-  g.key = make_uint2(v.x, v.y); g.nb = (int)(v.z & 0xFFFFu); g.nw = (int)(v.z >> 16);
+  g.key = make_uint2(v.x, v.y); g.nb = (int)(v.z & 0xFFFFu); g.nw = (int)(v.z >> 16); g.fw = v.w;
   return g;
 }
-__device__ __forceinline__ uint4 sk_pack(const SkGame& g) { return make_uint4(g.key.x, g.key.y, (uint32_t)g.nb | ((uint32_t)g.nw << 16), 0u); }
-
-// table entry of a position: key bits 0..44, black count, white count, and a top bit so that no entry is (0,0) = empty
-__device__ __forceinline__ uint2 sk_entry(uint2 key, int nb, int nw) {
-  return make_uint2(key.x, (key.y & 0x1FFFu) | ((uint32_t)nb << 13) | ((uint32_t)nw << 22) | 0x80000000u);
+__device__ __forceinline__ uint4 sk_pack(const SkGame& g) { return make_uint4(g.key.x, g.key.y, (uint32_t)g.nb | ((uint32_t)g.nw << 16), g.fw); }
+__device__ __forceinline__ SkGame sk_fresh() {   // a game on the empty board
+  SkGame g;
+  g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; g.fw = kNoPoint | (kNoPoint << 16);
+  return g;
 }
-__device__ __forceinline__ bool sk_real(uint2 e) { return (e.y >> 31) != 0u; }
-__device__ __forceinline__ int sk_count(uint2 e, int colour) { return (int)((e.y >> (colour ? 22 : 13)) & 511u); }
+
+// a table entry is the position's two keys; (0,0) is an empty slot
+__device__ __forceinline__ bool sk_real(uint2 e) { return (e.x | e.y) != 0u; }
 // start of the probe chain of the positions whose count of `colour` stones is `count`
 template <int N>
 __device__ __forceinline__ uint32_t sk_home(int colour, int count) {
-  return ((uint32_t)(2 * count + colour + 1) * 0x9E3779B1u) >> (32 - Zt<N>::LOG2);
+  return (((uint32_t)(2 * count + colour + 1) * 0x9E3779B1u) >> (32 - Zt<N>::LOG2)) & ~(Zt<N>::WIN - 1u);
 }
 // Table accesses go to the device-coherent level: a wavefront of the rollout kernel reads in a later ply what its own
 // lanes wrote in an earlier one.
@@ -764,12 +783,12 @@ __device__ __forceinline__ void wave_mem_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// XOR of the keys of the stones (black bits, white bits) of row r
+// XOR of the keys of the stones of row r: x over the black bits, y over the white bits
 template <int N>
 __device__ __forceinline__ uint2 row_keys(int r, uint32_t black, uint32_t white) {
   uint2 acc = make_uint2(0u, 0u);
-  for (uint32_t d = black; d; d &= d - 1u) { const uint2 k = zkey((uint32_t)(r * N + __ffs(d) - 1), 0u); acc.x ^= k.x; acc.y ^= k.y; }
-  for (uint32_t d = white; d; d &= d - 1u) { const uint2 k = zkey((uint32_t)(r * N + __ffs(d) - 1), 1u); acc.x ^= k.x; acc.y ^= k.y; }
+  for (uint32_t d = black; d; d &= d - 1u) acc.x ^= zkey((uint32_t)(r * N + __ffs(d) - 1), 0u);
+  for (uint32_t d = white; d; d &= d - 1u) acc.y ^= zkey((uint32_t)(r * N + __ffs(d) - 1), 1u);
   return acc;
 }
 
@@ -800,7 +819,7 @@ __device__ __forceinline__ int board_popcount(const Lane<N>& L, uint32_t w) {
   return sum;
 }
 
-// N consecutive table slots from `home`, one per row lane, loaded ahead of their use (home = ~0u: nothing loaded)
+// The WIN table slots from `home` on, one per row lane, loaded ahead of their use (home = ~0u: nothing loaded)
 struct SkWin {
   uint32_t home;
   uint2 e;
@@ -810,32 +829,31 @@ __device__ __forceinline__ SkWin sk_window(const Lane<N>& L, const uint2* tab, u
   SkWin w;
   w.home = want ? home : ~0u;
   w.e = make_uint2(1u, 0u);   // neither empty nor a real entry
-  if (L.valid && want) w.e = tab_load(&tab[(home + (uint32_t)L.r) & Zt<N>::MASK]);
+  if (L.valid && want && (uint32_t)L.r < Zt<N>::WIN) w.e = tab_load(&tab[(home + (uint32_t)L.r) & Zt<N>::MASK]);
   return w;
 }
 
 // Walks the probe chain that starts at `home` (the same for every lane of a board; active = this board takes part),
-// N slots per round, one per row lane, until the chain's first empty slot.  visit(e, look) is called once per round
+// WIN slots per round, one per row lane, until the chain's first empty slot.  visit(e, look) is called once per round
 // by every lane of the wavefront with the lane's entry (look = the lane holds a slot of an active board's chain).
 // free_slot = the first empty slot other than `taken` (a slot this ply has filled already; ~0u = none); ok = found,
-// which is always the case since the table is never full.  pre: windows loaded earlier, used when they start at `home`.
+// which is always the case since the table is never full.  pre: a window loaded earlier, used when it starts at `home`.
 template <int N, class V>
-__device__ __forceinline__ void sk_walk(const Lane<N>& L, const uint2* tab, uint32_t home, bool active, const SkWin (&pre)[3], uint32_t taken,
-                                        V&& visit, bool& ok, uint32_t& free_slot) {
+__device__ __forceinline__ void sk_walk(const Lane<N>& L, const uint2* tab, uint32_t home, bool active, const SkWin& pre, uint32_t taken, V&& visit,
+                                        bool& ok, uint32_t& free_slot) {
   using G = Geo<N>;
+  constexpr uint32_t WIN = Zt<N>::WIN;
   const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
   ok = false; free_slot = 0u;
   bool done = !active;
   uint32_t base = home;
-  for (uint32_t round = 0; round < Zt<N>::SLOTS / N + 2u; ++round) {
+  for (uint32_t round = 0; round < Zt<N>::SLOTS / WIN + 1u; ++round) {
     if (__ballot(!done) == 0ull) break;
-    const bool look = L.valid && !done;
+    const bool look = L.valid && (uint32_t)L.r < WIN && !done;
     uint2 e = make_uint2(1u, 0u);
     if (look) {
       const uint32_t slot = (base + (uint32_t)L.r) & Zt<N>::MASK;
-      if (round == 0u && pre[0].home == base) e = pre[0].e;
-      else if (round == 0u && pre[1].home == base) e = pre[1].e;
-      else if (round == 0u && pre[2].home == base) e = pre[2].e;
+      if (round == 0u && pre.home == base) e = pre.e;
       else e = tab_load(&tab[slot]);
       if (slot == taken && (e.x | e.y) == 0u) e = make_uint2(1u, 0u);
     }
@@ -843,29 +861,27 @@ __device__ __forceinline__ void sk_walk(const Lane<N>& L, const uint2* tab, uint
     const uint64_t em = __ballot(look && (e.x | e.y) == 0u) & seg;
     if (!done) {
       if (em) { free_slot = (base + (uint32_t)(__ffsll((long long)em) - 1 - (L.j * G::STRIDE + 1))) & Zt<N>::MASK; ok = true; done = true; }
-      else base += N;
+      else base += WIN;
     }
   }
 }
 
-// What a ply does to the game's key set (the same in every lane of the board).
+// What placing a stone does to the game's key set (the same in every lane of the board).
 struct SkPly {
-  uint2 key;        // key and counts of the position after the ply (meaningful for a board that placed a stone)
+  uint2 key;        // keys and counts of the position after the ply (meaningful for a board that placed a stone)
   int nb, nw;
-  uint2 entry;      // its table entry
-  bool found;       // that position is in the table already: the play is a repetition
   bool ok;          // free_a is valid
-  uint32_t free_a;  // where the entry goes on the chain of the mover's colour
+  uint32_t free_a;  // where the position goes on the chain of the mover's colour
 };
 
 // After the rules have been applied to a board that placed a stone (colour c, stones `captured` taken): the new
-// position's key, counts and entry, whether the table holds it already, and the free slot on its first chain.
+// position's keys and counts, and the free slot on its first chain.
 template <int N>
 __device__ __forceinline__ SkPly sk_look(const Lane<N>& L, const uint2* tab, const SkGame& g, int c, const Move& mv, uint32_t captured,
-                                         const SkWin (&pre)[3], uint32_t* scratch) {
+                                         const SkWin& pre, uint32_t* scratch) {
   SkPly s;
   const bool played = mv.playing;
-  const uint2 kp = zkey((uint32_t)(played ? mv.pr * N + mv.pc : 0), (uint32_t)c);
+  const uint32_t kp = zkey((uint32_t)(played ? mv.pr * N + mv.pc : 0), (uint32_t)c);
   int ncap = 0;
   uint2 dk = make_uint2(0u, 0u);
   if (__ballot(captured != 0u) != 0ull) {   // the captured stones have the other colour
@@ -873,13 +889,9 @@ __device__ __forceinline__ SkPly sk_look(const Lane<N>& L, const uint2* tab, con
     dk = board_xor<N>(L, row_keys<N>(L.r, c ? captured : 0u, c ? 0u : captured), scratch);
   }
   const int own1 = (c ? g.nw : g.nb) + 1, opp1 = (c ? g.nb : g.nw) - ncap;
-  s.key = make_uint2(g.key.x ^ kp.x ^ dk.x, g.key.y ^ kp.y ^ dk.y);
+  s.key = make_uint2(g.key.x ^ (c ? 0u : kp) ^ dk.x, g.key.y ^ (c ? kp : 0u) ^ dk.y);
   s.nb = c ? opp1 : own1; s.nw = c ? own1 : opp1;
-  s.entry = sk_entry(s.key, s.nb, s.nw);
-  bool hit = false;
-  sk_walk<N>(L, tab, sk_home<N>(c, own1), played, pre, ~0u,
-             [&](uint2 e, bool look) { hit = hit || (look && e.x == s.entry.x && e.y == s.entry.y); }, s.ok, s.free_a);
-  s.found = played && board_any(hit, L.seglo, L.seghi);
+  sk_walk<N>(L, tab, sk_home<N>(c, own1), played, pre, ~0u, [](uint2, bool) {}, s.ok, s.free_a);
   return s;
 }
 
@@ -887,68 +899,46 @@ __device__ __forceinline__ SkPly sk_look(const Lane<N>& L, const uint2* tab, con
 // tab_r: the table the chains are read from; tab_w: the one the entries go to (they differ only while the slot kernel
 // copies a game from one slot to another).
 template <int N>
-__device__ __forceinline__ void sk_insert(const Lane<N>& L, const uint2* tab_r, uint2* tab_w, uint4* zcur_of_board, SkGame& g, const SkPly& s, bool insert,
-                                          int c, const SkWin (&pre)[3]) {
+__device__ __forceinline__ void sk_insert(const Lane<N>& L, const uint2* tab_r, uint2* tab_w, SkGame& g, const SkPly& s, bool insert, int c,
+                                          const SkWin& pre) {
   if (__ballot(insert) == 0ull) return;
   bool ok_c;
   uint32_t free_c;
   const int opp1 = c ? s.nb : s.nw;   // count of the colour that did not move
   sk_walk<N>(L, tab_r, sk_home<N>(c ^ 1, opp1), insert, pre, s.ok ? s.free_a : ~0u, [](uint2, bool) {}, ok_c, free_c);
   if (insert) { g.key = s.key; g.nb = s.nb; g.nw = s.nw; }
-  if (insert && L.valid && L.r == 0) {
-    if (s.ok) tab_store(&tab_w[s.free_a], s.entry);
-    if (ok_c) tab_store(&tab_w[free_c], s.entry);
-    *zcur_of_board = sk_pack(g);
+  if (insert && L.valid && L.r == 0 && sk_real(s.key)) {
+    if (s.ok) tab_store(&tab_w[s.free_a], s.key);
+    if (ok_c) tab_store(&tab_w[free_c], s.key);
   }
   wave_mem_fence();
 }
 
-// The plays of the mover (colour c2) that would recreate the earlier position with entry q (act = this board has such
-// an entry to look at), as row words.
+// Whether the mover's (colour c2) play on point p would recreate the earlier position whose keys differ from the
+// current ones by d_other in the other colour (on = this board has such a candidate); returns the play as row words.
 template <int N>
-__device__ __forceinline__ uint32_t sk_forbidden_by(const Lane<N>& L, const Row<N>& R, const SkGame& g, int c2, uint2 q, bool act, uint32_t legal_s,
-                                                    uint32_t capc, uint32_t* scratch) {
-  using G = Geo<N>;
-  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
-  const uint32_t dx = q.x ^ g.key.x, dy = (q.y ^ g.key.y) & 0x1FFFu;   // key of (earlier position) xor (current position)
-  const int diff = (c2 ? g.nb : g.nw) - sk_count(q, c2 ^ 1);           // stones of the other colour the play would have to take
-  const bool plain = act && diff == 0, taking = act && diff > 0;
-  uint32_t forb = 0u;
-  if (__ballot(plain) != 0ull) {   // a play that takes nothing: the two positions differ by that one stone
-    for (uint32_t d = plain ? (legal_s & ~capc) : 0u; d; d &= d - 1u) {
-      const uint2 k = zkey((uint32_t)(L.r * N + __ffs(d) - 1), (uint32_t)c2);
-      if (k.x == dx && (k.y & 0x1FFFu) == dy) forb |= d & (0u - d);
-    }
+__device__ __forceinline__ uint32_t sk_forbidden_play(const Lane<N>& L, const Row<N>& R, int c2, int p, uint32_t d_other, bool on, uint32_t legal_s,
+                                                      uint32_t* scratch) {
+  const int pr = on ? p / N : -100, pc = on ? p - (p / N) * N : 0;
+  const uint32_t pb = (L.valid && L.r == pr) ? (1u << pc) : 0u;
+  const bool legal = on && board_any((legal_s & pb) != 0u, L.seglo, L.seghi);   // an occupied, suicidal or ko point is out anyway
+  const uint32_t aopp = c2 ? R.ab : R.aw;
+  const uint32_t seed = legal ? (dilate(pb) & aopp) : 0u;    // the opposing chains in atari next to the play are what it takes
+  const bool takes = board_any(seed != 0u, L.seglo, L.seghi);
+  uint32_t kt = 0u;
+  if (__ballot(takes) != 0ull) {
+    const uint32_t taken = flood_plain(seed, aopp);
+    const uint2 k = board_xor<N>(L, row_keys<N>(L.r, c2 ? taken : 0u, c2 ? 0u : taken), scratch);
+    kt = c2 ? k.x : k.y;
   }
-  if (__ballot(taking) != 0ull) {  // a play that takes stones: try each of the board's capturing plays in turn
-    const uint32_t aopp = c2 ? R.ab : R.aw;
-    uint32_t rem = taking ? capc : 0u;
-    for (;;) {
-      const uint64_t nz = __ballot(rem != 0u);
-      if (nz == 0ull) break;
-      const uint64_t mine = nz & seg;
-      const bool on = mine != 0ull;
-      const int src = on ? (__ffsll((long long)mine) - 1) : L.lane;
-      const uint32_t low = rem & (0u - rem);
-      const uint32_t pb = (on && L.lane == src) ? low : 0u;            // the play as a row word of its board
-      const int pcol = __shfl((int)(__ffs(low) - 1), src);
-      const int prow = src - (L.j * G::STRIDE + 1);
-      const uint32_t taken = flood_plain(dilate(pb) & aopp, aopp);     // the chains in atari next to it
-      const int size = board_popcount<N>(L, taken);
-      const uint2 kt = board_xor<N>(L, row_keys<N>(L.r, c2 ? taken : 0u, c2 ? 0u : taken), scratch);
-      const uint2 kp = zkey((uint32_t)(on ? prow * N + pcol : 0), (uint32_t)c2);
-      if (on && size == diff && (kt.x ^ kp.x) == dx && ((kt.y ^ kp.y) & 0x1FFFu) == dy) forb |= pb;
-      rem &= ~pb;
-    }
-  }
-  return forb;
+  return (legal && kt == d_other) ? pb : 0u;
 }
 
 // The plays of the player to move that would recreate an earlier position of the game (row words): one walk of the
 // chain of the positions with one more stone of the mover's colour than now.
 template <int N>
 __device__ __forceinline__ uint32_t sk_forbidden(const Lane<N>& L, const uint2* tab, const SkGame& g, const Row<N>& R, const Meta& m, bool active,
-                                                 const SkWin (&pre)[3], uint32_t* scratch) {
+                                                 const SkWin& pre, uint32_t* scratch) {
   uint32_t forb = 0u;
   if (__ballot(active) == 0ull) return forb;
   const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
@@ -957,40 +947,124 @@ __device__ __forceinline__ uint32_t sk_forbidden(const Lane<N>& L, const uint2* 
   uint32_t fs;
   sk_walk<N>(L, tab, sk_home<N>(c2, n2 + 1), active, pre, ~0u,
              [&](uint2 e, bool look) {
-               uint64_t pend = __ballot(look && sk_real(e) && sk_count(e, c2) == n2 + 1);
-               if (pend == 0ull) return;          // nearly always: no earlier position has that count
+               // is (entry xor current) in the mover's colour the key of one stone of that colour?
+               const uint32_t u = zkey_inverse(c2 ? e.y ^ g.key.y : e.x ^ g.key.x) - 1u;   // 2*point + colour for a stone key
+               const uint32_t d_other = c2 ? e.x ^ g.key.x : e.y ^ g.key.y;
+               uint64_t pend = __ballot(look && sk_real(e) && u < 2u * N * N && (int)(u & 1u) == c2);
+               if (pend == 0ull) return;          // nearly always: no earlier position is one stone of the mover's away
                const uint32_t legal_s = legal_row<N>(L, R, m.wtm, m.ko);
-               const uint32_t capc = legal_s & dilate(c2 ? R.ab : R.aw);   // plays that take stones: next to an opposing chain in atari
-               while (pend != 0ull) {             // one earlier position per board per turn
+               while (pend != 0ull) {             // one candidate per board per turn
                  const uint64_t mine = pend & seg;
-                 const bool act = mine != 0ull;
-                 const int src = act ? (__ffsll((long long)mine) - 1) : L.lane;
-                 const uint2 q = make_uint2((uint32_t)__shfl((int)e.x, src), (uint32_t)__shfl((int)e.y, src));
-                 pend &= ~__ballot(act && L.lane == src);
-                 forb |= sk_forbidden_by<N>(L, R, g, c2, q, act, legal_s, capc, scratch);
+                 const bool on = mine != 0ull;
+                 const int src = on ? (__ffsll((long long)mine) - 1) : L.lane;
+                 const int p = __shfl((int)(u >> 1), src);
+                 const uint32_t dq = (uint32_t)__shfl((int)d_other, src);
+                 pend &= ~__ballot(on && L.lane == src);
+                 forb |= sk_forbidden_play<N>(L, R, c2, p, dq, on, legal_s, scratch);
                }
              },
              ok, fs);
   return forb;
 }
 
+// the forbidden plays kept with a game -> row words of this lane's board
+template <int N>
+__device__ __forceinline__ uint32_t sk_forb_rows(const Lane<N>& L, uint32_t fw) {
+  const uint32_t p1 = fw & 0xFFFFu, p2 = fw >> 16;
+  uint32_t out = 0u;
+  if (L.valid && p1 < (uint32_t)(N * N) && (int)(p1 / N) == L.r) out |= 1u << (p1 % N);
+  if (L.valid && p2 < (uint32_t)(N * N) && (int)(p2 / N) == L.r) out |= 1u << (p2 % N);
+  return out;
+}
+// row words -> the form kept with the game (the same in every lane of the board)
+template <int N>
+__device__ __forceinline__ uint32_t sk_forb_word(const Lane<N>& L, uint32_t forb) {
+  using G = Geo<N>;
+  uint32_t fw = kNoPoint | (kNoPoint << 16);
+  if (__ballot(forb != 0u) == 0ull) return fw;   // nearly always
+  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
+  const int cnt = board_popcount<N>(L, forb);
+  uint32_t rest = forb;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const uint64_t mine = __ballot(rest != 0u) & seg;
+    const int src = mine ? (__ffsll((long long)mine) - 1) : L.lane;
+    const int col = __shfl((int)(__ffs(rest) - 1), src);
+    const uint32_t p = mine ? (uint32_t)((src - (L.j * G::STRIDE + 1)) * N + col) : kNoPoint;
+    fw = k == 0 ? ((fw & 0xFFFF0000u) | p) : ((fw & 0xFFFFu) | (p << 16));
+    if (L.lane == src) rest &= rest - 1u;
+  }
+  if (cnt > 2) fw = kLookAgain | (kNoPoint << 16);
+  return fw;
+}
+// The forbidden plays of the position the kernel has just loaded: from the game's record, or (more than two of them
+// were found when the position arose) by walking the table again.
+template <int N>
+__device__ __forceinline__ uint32_t sk_forb_loaded(const Lane<N>& L, const uint2* tab, const SkGame& g, const Row<N>& R, const Meta& m, const SkWin& pre,
+                                                   uint32_t* scratch) {
+  uint32_t forb = sk_forb_rows<N>(L, g.fw);
+  const bool again = L.boardok && (g.fw & 0xFFFFu) == kLookAgain;
+  if (__ballot(again) != 0ull) {
+    const uint32_t f2 = sk_forbidden<N>(L, tab, g, R, m, again, pre, scratch);
+    if (again) forb = f2;
+  }
+  return forb;
+}
+
 // all lanes of the wavefront clear the tables of the boards flagged by their row-0 lane (auto-reset); `game` = the
 // index of this lane's board among the handle's tables
 template <int N>
-__device__ __forceinline__ void sk_clear_tables(const Lane<N>& L, bool flagged, uint2* zt, uint4* zcur, int game) {
+__device__ __forceinline__ void sk_clear_tables(const Lane<N>& L, bool flagged, uint2* zt, int game) {
   for (uint64_t q = __ballot(flagged && L.valid && L.r == 0); q; q &= q - 1ull) {
     const size_t bb = (size_t)__shfl(game, __ffsll((long long)q) - 1);
     uint4* t4 = (uint4*)(zt + bb * Zt<N>::SLOTS);
     for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) t4[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (L.lane == 0) zcur[bb] = make_uint4(0u, 0u, 0u, 0u);
   }
   wave_mem_fence();
 }
 
-// One ply with the repetition rule.  Same steps as go_step_kernel; in addition the position after the move is looked
-// up in the game's table before the move is accepted, and (mode 2) the next mover's repeating plays leave the mask.
+// Steps a2-a8 of one ply with the repetition rule for every board of the wavefront: the requested move passes the
+// legality gate only if it is not one of the position's forbidden plays (`forb`, updated to those of the new position),
+// the new position goes into the table, an auto-reset clears it.  tab_r / tab_w / game: see sk_insert, sk_clear_tables.
+// GATE as in gate_move.  Out: as apply_move.
+template <int N, bool GATE>
+__device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& m, SkGame& g, uint32_t& forb, const Rules& rules, bool skip, bool want_pass,
+                                             bool want_point, int pr_in, int pc_in, const uint2* tab_r, uint2* tab_w, uint2* zt, int game,
+                                             uint32_t* scratch, float& rew0, float& rew1, bool& flag, bool pre_a_loaded, const SkWin& pre_a) {
+  const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
+  Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
+  // a play the simple rules allow but the repetition rule forbids is an illegal action
+  const uint32_t pbit = (L.valid && mv.playing && L.r == mv.pr) ? (1u << mv.pc) : 0u;
+  const bool repeats = mv.playing && board_any((pbit & forb) != 0u, L.seglo, L.seghi);
+  if (repeats) { mv.playing = false; mv.illegal = true; mv.pr = -100; mv.pc = 0; }
+  // The chains this ply needs start at slots known before the rules run when the move takes nothing (most do): the
+  // loads fly while the rules run.  pre[0]: one more stone of the mover's colour (where the new position goes);
+  // pre[1]: one more stone of the other colour (the next mover's forbidden plays); pre[2]: as many stones of the
+  // other colour as now (the new position's second entry).
+  SkWin pre[3];
+  if (pre_a_loaded) pre[0] = pre_a;
+  else pre[0] = sk_window<N>(L, tab_r, sk_home<N>(c, own + 1), mv.playing);
+  pre[1] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp + 1), mv.playing || mv.is_pass);
+  pre[2] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp), mv.playing);
+  Rules r0 = rules;
+  r0.auto_reset = 0;   // the reset happens below, after the table work
+  bool reset;
+  uint32_t captured;
+  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
+  const SkPly s = sk_look<N>(L, tab_r, g, c, mv, captured, pre[0], scratch);
+  const bool do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
+  sk_insert<N>(L, tab_r, tab_w, g, s, mv.playing && !do_reset, c, pre[2]);
+  // the forbidden plays change with the position and with the player to move; otherwise they stay
+  const bool moved = (mv.playing || mv.is_pass) && !do_reset;
+  const uint32_t fresh = sk_forbidden<N>(L, tab_r, g, R, m, moved, pre[1], scratch);
+  if (moved) forb = fresh;
+  if (do_reset) { reset_board<N>(L, R, m, rules.seed); g = sk_fresh(); forb = 0u; }
+  sk_clear_tables<N>(L, do_reset, zt, game);
+}
+
+// One ply with the repetition rule.  Same steps as go_step_kernel.
 template <int N, bool TIGHT>
-__global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur, int mode) {
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur, int mode) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -1003,65 +1077,33 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel
   load_row<N>(a.planes, rows_total, L, R);
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
-  SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
+  SkGame g = L.boardok ? sk_unpack(zcur[L.b]) : sk_fresh();
   fill_spread_table(lut);
   if (wave * a.wb >= a.B) return;
-  const Row<N> R_loaded = R;
   Meta m = unpack_meta(meta_raw);
-  const Meta m_loaded = m;
   uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
 
   const bool skip = !L.boardok || act == -1;
   const bool in_range = act >= 0 && act < G::P;
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
-  const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
-
-  // The three chains this ply may need start at slots known before the rules run when the move takes nothing (most do):
-  // the loads fly while the rules run.  pre[0]: positions with one more stone of the mover's colour (the played move's
-  // look-up and first insert; also the mover's own forbidden plays when the board does not move); pre[1]: one more
-  // stone of the other colour (the next mover's forbidden plays); pre[2]: as many stones of the other colour as now
-  // (second insert).
-  const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
-  SkWin pre[3];
-  pre[0] = sk_window<N>(L, tab, sk_home<N>(c, own + 1), L.boardok);
-  pre[1] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp + 1), L.boardok && mode == 2);
-  pre[2] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp), mv.playing);
-
-  // the move is applied (captures included, no reset yet), then the new position is looked up
-  Rules r0 = a.rules;
-  r0.auto_reset = 0;
+  SkWin none;
+  none.home = ~0u; none.e = make_uint2(1u, 0u);
+  uint32_t forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
   float rew0, rew1;
-  bool flag, reset;
-  uint32_t captured;
-  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
-  const SkPly s = sk_look<N>(L, tab, g, c, mv, captured, pre, lds_mask_all[wib]);
-  const bool violate = s.found;
-  if (__ballot(violate) != 0ull) {   // rare: redo the ply of this wavefront's boards with the offending moves turned illegal
-    R = R_loaded;
-    m = m_loaded;
-    Move mv2 = mv;
-    if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
-    apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
-  }
+  bool flag;
+  sk_step_core<N, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none);
   if (!skip && L.valid && L.r == 0) {
     *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
-  // a8: auto-reset, here instead of inside apply_move; the game's table is cleared by the whole wavefront
-  const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
-  sk_insert<N>(L, tab, tab, &zcur[L.boardok ? L.b : 0], g, s, mv.playing && !violate && !do_reset, c, pre);
-  uint32_t forb = 0u;
-  if (mode == 2) forb = sk_forbidden<N>(L, tab, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
-  if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
-  sk_clear_tables<N>(L, do_reset, zt, zcur, L.b);
+  g.fw = sk_forb_word<N>(L, forb);
 
   if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(mode == 2 ? forb : 0u);
   if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
   if (!skip) {
-    if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
-    else store_row<N>(a.planes, rows_total, L, R);
-    if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+    store_row<N>(a.planes, rows_total, L, R);
+    if (L.valid && L.r == 0) { a.meta[L.b] = pack_meta(m); zcur[L.b] = sk_pack(g); }
   }
   if (a.next_actions) {
     const bool wait = L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
@@ -1070,18 +1112,19 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 4) go_step_superko_kernel
   }
 }
 
-// Fills the tables from what the state still carries: the 8 history positions and the current one (set-up, import).
-// The tables must have been cleared by an earlier launch.
+// Fills the tables from what the state still carries: the 8 history positions and the current one (set-up, import),
+// and finds the current position's forbidden plays.  The tables must have been cleared by an earlier launch.
 template <int N>
-__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, int B, uint2* zt, uint4* zcur) {
+__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, const uint4* meta, int B, uint2* zt, uint4* zcur) {
   __shared__ uint32_t scratch[64];
   const Lane<N> L(blockIdx.x, threadIdx.x, B);
   Row<N> R;
   load_row<N>(planes, (size_t)B * N, L, R);
+  const Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
   uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
-  SkWin none[3];
-  none[0].home = none[1].home = none[2].home = ~0u;
-  none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
+  SkWin none;
+  none.home = ~0u; none.e = make_uint2(1u, 0u);
+  SkGame g = sk_fresh();
   for (int i = 8; i >= 0; --i) {   // history position i-1 (oldest first), then i = 0: the current stones
     uint32_t black = R.bk, white = R.wt;
     if (i > 0) {
@@ -1095,23 +1138,23 @@ __global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* pla
     }
     uint2 k = make_uint2(0u, 0u);
     if (L.valid) k = row_keys<N>(L.r, black, white);
-    SkGame g;
     g.key = board_xor<N>(L, k, scratch);
     g.nb = board_popcount<N>(L, black); g.nw = board_popcount<N>(L, white);
-    const uint2 entry = sk_entry(g.key, g.nb, g.nw);
+    const uint2 entry = g.key;
     bool hit = false, ok_a, ok_b;
     uint32_t free_a, free_b;
     sk_walk<N>(L, tab, sk_home<N>(0, g.nb), L.boardok, none, ~0u, [&](uint2 e, bool look) { hit = hit || (look && e.x == entry.x && e.y == entry.y); },
                ok_a, free_a);
-    const bool found = board_any(hit, L.seglo, L.seghi);
+    const bool found = board_any(hit, L.seglo, L.seghi) || !sk_real(entry);   // the empty board is never stored
     sk_walk<N>(L, tab, sk_home<N>(1, g.nw), L.boardok && !found, none, ok_a ? free_a : ~0u, [](uint2, bool) {}, ok_b, free_b);
     if (L.valid && L.r == 0) {
       if (!found && ok_a) tab_store(&tab[free_a], entry);
       if (!found && ok_b) tab_store(&tab[free_b], entry);
-      if (i == 0) zcur[L.b] = sk_pack(g);
     }
     __threadfence();   // the next round's look-ups must see these inserts
   }
+  g.fw = sk_forb_word<N>(L, sk_forbidden<N>(L, tab, g, R, m, L.boardok, none, scratch));
+  if (L.valid && L.r == 0) zcur[L.b] = sk_pack(g);
 }
 
 __global__ void go_zero_kernel(uint4* p, size_t n16) {
@@ -1169,50 +1212,34 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
   const bool skip = !L.boardok || act == -1;
   const bool in_range = act >= 0 && act < G::P;
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
-  const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
   float rew0, rew1;
-  bool flag, reset;
-  uint32_t captured;
+  bool flag;
   uint32_t forb = 0u;
   if constexpr (!SK) {
+    const Move mv = gate_move<N, true>(L, R, m, skip, act == G::P, in_range, pr, pc);
+    bool reset;
+    uint32_t captured;
     apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
   } else {
     const int sslot = L.boardok ? src : 0, dslot = L.boardok ? dst : 0;
-    SkGame g = sk_unpack(L.boardok ? a.zcur[sslot] : make_uint4(0u, 0u, 0u, 0u));
+    SkGame g = L.boardok ? sk_unpack(a.zcur[sslot]) : sk_fresh();
     const uint2* tab_r = a.zt + (size_t)sslot * Zt<N>::SLOTS;   // nothing writes to a source slot's table during the call
     uint2* tab_w = a.zt + (size_t)dslot * Zt<N>::SLOTS;
-    const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
-    SkWin pre[3];
-    pre[0] = sk_window<N>(L, tab_r, sk_home<N>(c, own + 1), L.boardok);
-    pre[1] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp + 1), L.boardok && a.sk_mode == 2);
-    pre[2] = sk_window<N>(L, tab_r, sk_home<N>(c ^ 1, opp), mv.playing);
     for (uint64_t q = __ballot(L.valid && L.r == 0 && src != dst); q; q &= q - 1ull) {   // all lanes copy one table after the other
       const int ln = __ffsll((long long)q) - 1;
       const uint4* from = (const uint4*)(a.zt + (size_t)__shfl(sslot, ln) * Zt<N>::SLOTS);
       uint4* to = (uint4*)(a.zt + (size_t)__shfl(dslot, ln) * Zt<N>::SLOTS);
       for (uint32_t i = L.lane; i < Zt<N>::SLOTS / 2u; i += 64u) to[i] = from[i];
     }
-    const Row<N> R_loaded = R;
-    const Meta m_loaded = m;
-    Rules r0 = a.rules;
-    r0.auto_reset = 0;
-    apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
-    const SkPly s = sk_look<N>(L, tab_r, g, c, mv, captured, pre, lds_mask_all[wib]);
-    const bool violate = s.found;
-    if (__ballot(violate) != 0ull) {   // rare: redo the ply with the repeating plays turned illegal
-      R = R_loaded;
-      m = m_loaded;
-      Move mv2 = mv;
-      if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
-      apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
-    }
-    const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
     __threadfence();   // the copied tables are in place before entries are added to them or they are cleared
-    sk_insert<N>(L, tab_r, tab_w, &a.zcur[dslot], g, s, mv.playing && !violate && !do_reset, c, pre);
-    if (a.sk_mode == 2) forb = sk_forbidden<N>(L, tab_r, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
-    if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
-    sk_clear_tables<N>(L, do_reset, a.zt, a.zcur, dslot);
-    if (L.valid && L.r == 0 && !do_reset) a.zcur[dslot] = sk_pack(g);
+    SkWin none;
+    none.home = ~0u; none.e = make_uint2(1u, 0u);
+    forb = sk_forb_loaded<N>(L, tab_r, g, R, m, none, lds_mask_all[wib]);
+    sk_step_core<N, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, false,
+                          none);
+    g.fw = sk_forb_word<N>(L, forb);
+    if (L.valid && L.r == 0) a.zcur[dslot] = sk_pack(g);
+    if (a.sk_mode != 2) forb = 0u;   // the mask shows the simple-ko set unless the rule proper is on
   }
   if ((threadIdx.x & 63) == L.j * G::STRIDE + 1 && L.j < G::W && L.b < a.n) {   // row-0 lane of the entry, inert or not
     if (bad) { if (a.term) a.term[L.b] = 255; }
@@ -1273,15 +1300,16 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
   Meta m = unpack_meta(L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
   const int64_t start = (L.boardok && a.start_t) ? (int64_t)a.start_t[L.b] : INT64_MIN;
   uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  SkGame g;
+  SkGame g = sk_fresh();
   uint2* tab = nullptr;
-  SkWin pre[3];
+  uint32_t forb = 0u;
   if constexpr (SK) {
-    g = sk_unpack(L.boardok ? a.zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
+    if (L.boardok) g = sk_unpack(a.zcur[L.b]);
     tab = a.zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
-    pre[0].home = pre[1].home = pre[2].home = ~0u;
-    pre[0].e = pre[1].e = pre[2].e = make_uint2(1u, 0u);
-    if (a.sk_mode == 2) legal &= ~sk_forbidden<N>(L, tab, g, R, m, L.boardok, pre, lds_mask_all[wib]);
+    SkWin none;
+    none.home = ~0u; none.e = make_uint2(1u, 0u);
+    forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
+    if (a.sk_mode == 2) legal &= ~forb;
   }
   int slice = 0;
   for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
@@ -1295,34 +1323,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       step_core<N, false>(L, R, m, a.rules, skip, d.pass, d.point, d.pr, d.pc, rew0, rew1, flag);
       legal = legal_row<N>(L, R, m.wtm, m.ko);
     } else {
-      const Move mv = gate_move<N, false>(L, R, m, skip, d.pass, d.point, d.pr, d.pc);
-      const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
-      pre[0] = sk_window<N>(L, tab, sk_home<N>(c, own + 1), L.boardok);
-      pre[1] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp + 1), L.boardok && a.sk_mode == 2);
-      pre[2] = sk_window<N>(L, tab, sk_home<N>(c ^ 1, opp), mv.playing);
-      const Row<N> R_before = R;
-      const Meta m_before = m;
-      Rules r0 = a.rules;
-      r0.auto_reset = 0;
-      bool reset;
-      uint32_t captured;
-      apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
-      const SkPly s = sk_look<N>(L, tab, g, c, mv, captured, pre, lds_mask_all[wib]);
-      const bool violate = s.found;   // possible only where the mask shows the simple-ko set (mode 1)
-      if (__ballot(violate) != 0ull) {
-        R = R_before;
-        m = m_before;
-        Move mv2 = mv;
-        if (violate) { mv2.playing = false; mv2.illegal = true; mv2.pr = -100; mv2.pc = 0; }
-        apply_move<N>(L, R, m, r0, mv2, rew0, rew1, flag, captured, reset);
-      }
-      const bool do_reset = !skip && !mv.frozen && m.term && a.rules.auto_reset != 0;
-      sk_insert<N>(L, tab, tab, &a.zcur[L.boardok ? L.b : 0], g, s, mv.playing && !violate && !do_reset, c, pre);
-      uint32_t forb = 0u;
-      if (a.sk_mode == 2) forb = sk_forbidden<N>(L, tab, g, R, m, L.boardok && !do_reset, pre, lds_mask_all[wib]);
-      if (do_reset) { reset_board<N>(L, R, m, a.rules.seed); g.key = make_uint2(0u, 0u); g.nb = 0; g.nw = 0; }
-      sk_clear_tables<N>(L, do_reset, a.zt, a.zcur, L.b);
-      legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
+      SkWin none;
+      none.home = ~0u; none.e = make_uint2(1u, 0u);
+      sk_step_core<N, false>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none);
+      legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(a.sk_mode == 2 ? forb : 0u);
     }
     const size_t sb = (size_t)slice * a.B;
     if (L.valid && L.r == 0) {
@@ -1339,6 +1343,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
   }
   store_row<N>(a.planes, rows_total, L, R);
   if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+  if constexpr (SK) {
+    g.fw = sk_forb_word<N>(L, forb);
+    if (L.valid && L.r == 0) a.zcur[L.b] = sk_pack(g);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1364,11 +1372,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint
   uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
   if constexpr (SK) {
     if (mask) {
-      const SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
-      SkWin none[3];
-      none[0].home = none[1].home = none[2].home = ~0u;
-      none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
-      legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, lds_mask_all[wib]);
+      const SkGame g = L.boardok ? sk_unpack(zcur[L.b]) : sk_fresh();
+      SkWin none;
+      none.home = ~0u; none.e = make_uint2(1u, 0u);
+      legal &= ~sk_forb_loaded<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, none, lds_mask_all[wib]);
     }
   }
   emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, B, mask, mask_pitch, obs, obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut);
@@ -1402,11 +1409,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(
   Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u));
   uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
   if constexpr (SK) {
-    const SkGame g = sk_unpack(L.boardok ? zcur[L.b] : make_uint4(0u, 0u, 0u, 0u));
-    SkWin none[3];
-    none[0].home = none[1].home = none[2].home = ~0u;
-    none[0].e = none[1].e = none[2].e = make_uint2(1u, 0u);
-    legal &= ~sk_forbidden<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, L.boardok, none, sk_scratch[wave_in_block()]);
+    const SkGame g = L.boardok ? sk_unpack(zcur[L.b]) : sk_fresh();
+    SkWin none;
+    none.home = ~0u; none.e = make_uint2(1u, 0u);
+    legal &= ~sk_forb_loaded<N>(L, zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS, g, R, m, none, sk_scratch[wave_in_block()]);
   }
   const bool wait = L.boardok && start_t && (int64_t)t < (int64_t)start_t[L.b];
   const Draw<N> d = draw_action<N>(L, legal, seed, t, wait);
@@ -1744,7 +1750,7 @@ int launch_superko_refresh(pgxgo_ctx* h, bool rebuild) {
   hipLaunchKernelGGL(go_zero_kernel, dim3(blocks), dim3(256), 0, h->stream, (uint4*)h->zt, n16);
   HIPCHK(hipGetLastError());
   if (rebuild) {
-    hipLaunchKernelGGL(go_superko_rebuild_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->B, h->zt, h->zcur);
+    hipLaunchKernelGGL(go_superko_rebuild_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, h->zt, h->zcur);
     HIPCHK(hipGetLastError());
   }
   return PGXGO_OK;
@@ -1860,8 +1866,8 @@ int pgxgo_reset(pgxgo_t h) {
   if (!h) return PGXGO_EINVAL;
   int rc = DISPATCH_N(h, launch_reset<19>(h, 0), launch_reset<9>(h, 0));
   if (rc != PGXGO_OK) return rc;
-  if (h->zt) {
-    rc = DISPATCH_N(h, launch_superko_refresh<19>(h, false), launch_superko_refresh<9>(h, false));
+  if (h->zt) {   // empty tables; the rebuild pass writes the per-game records of the fresh games
+    rc = DISPATCH_N(h, launch_superko_refresh<19>(h, true), launch_superko_refresh<9>(h, true));
     if (rc != PGXGO_OK) return rc;
   }
   if (h->mask_out || h->obs_out) return DISPATCH_N(h, launch_emit<19>(h, h->mask_out, h->obs_out), launch_emit<9>(h, h->mask_out, h->obs_out));

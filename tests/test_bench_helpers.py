@@ -31,3 +31,20 @@ def test_more_than_one_gpu_is_refused():
     import sys
     r = subprocess.run([sys.executable, bench.__file__, "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+
+
+def test_rotation_and_default_steps():
+    go3 = 16384 * (362 + 361 * 17)
+    assert bench.rotation_slices(go3) == 8 and bench.rotation_slices(4 * go3) == 2 and bench.rotation_slices(100) == 8
+    assert bench.rotation_slices(go3) * go3 > 3 * bench.MEMORY_SIDE_CACHE          # a rotation writes far beyond the memory-side cache
+    c = workloads.CONFIGS
+    assert bench.default_steps(c[3]) == 2000 and bench.default_steps(c[1]) == 1000 and bench.default_steps(c[4]) == 500
+    for cfg in (c[0], c[2], workloads.HEX_CONFIGS[0]):                                # without auto-reset the timed windows end before the games do
+        assert cfg.warmup_max + cfg.preroll + 20 + 2 * bench.default_steps(cfg) <= cfg.steps
+    assert c[3].preroll >= 600 and c[4].warmup_max == 300                           # the timed plies lie in the dense regime
+
+
+def test_bound_statement_rule():
+    assert bench.bound_statement(6.0, 5.0, 1.0, 0.1)["bound_by"].startswith("launch gap")
+    assert bench.bound_statement(22.0, 5.5, 17.0, 5.3)["bound_by"].startswith("hbm")
+    assert bench.bound_statement(40.0, 5.0, 23.0, 51.0)["bound_by"] == "valu issue"
