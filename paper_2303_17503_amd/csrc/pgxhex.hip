@@ -382,30 +382,9 @@ constexpr int LANE_OBS_DW = ((15 + 64 * OBS + 31) / 32 + 3) / 4 * 4;
 constexpr int LANE_MASK_ROUNDS = (64 * A / 16 + 63) / 64;
 constexpr int LANE_OBS_ROUNDS = (64 * OBS / 16 + 63) / 64;
 
-template <bool SAMPLE>
-__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(StepArgs a) {
-  __shared__ uint2 lut[256];
-  __shared__ uint32_t lut4[256];
-  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][LANE_OBS_DW];
-  __shared__ __align__(16) uint32_t lds_mask[kWavesPerBlock][LANE_MASK_DW];
-  const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
-  const int b0 = wave * 64;                 // first board of the wavefront
-  const int b = b0 + lane;
-  const bool ok = b < a.B;
-  // state: 11 row words (black bits 0-10, white bits 16-26), the scalar record, the action
-  uint32_t row[N];
-#pragma unroll
-  for (int r = 0; r < N; ++r) row[r] = ok ? a.rows[(size_t)b * N + r] : 0u;
-  const uint4 mv = ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u);
-  const int act = ok ? a.actions[b] : -1;
-  fill_spread4_table(lut4);
-  fill_spread_table(lut);                   // ends with the block's only barrier
-  if (b0 >= a.B) return;
-  const int nb = a.B - b0 < 64 ? a.B - b0 : 64;
-  Meta m = unpack_meta(mv);
-
-  B128 bk = {{0u, 0u, 0u, 0u}}, wt = {{0u, 0u, 0u, 0u}};
+// rows (black bits 0-10, white bits 16-26 of one dword per row) <-> the two sets of a board
+__device__ __forceinline__ void rows_to_sets(const uint32_t (&row)[N], B128& bk, B128& wt) {
+  bk = B128{{0u, 0u, 0u, 0u}}; wt = bk;
 #pragma unroll
   for (int r = 0; r < N; ++r) {
     const int i = (N * r) >> 5, s = (N * r) & 31;
@@ -413,13 +392,30 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
     bk.w[i] |= kb << s; wt.w[i] |= kw << s;
     if (s + N > 32) { bk.w[i + 1] |= kb >> (32 - s); wt.w[i + 1] |= kw >> (32 - s); }
   }
+}
+__device__ __forceinline__ void store_sets_as_rows(uint32_t* rows_of_board, const B128& bk, const B128& wt) {
+#pragma unroll
+  for (int r = 0; r < N; ++r) {
+    const int i = (N * r) >> 5, s = (N * r) & 31;
+    uint32_t kb = bk.w[i] >> s, kw = wt.w[i] >> s;
+    if (s + N > 32) { kb |= bk.w[i + 1] << (32 - s); kw |= wt.w[i + 1] << (32 - s); }
+    rows_of_board[r] = (kb & FULL) | ((kw & FULL) << 16);
+  }
+}
 
-  // ---- a1-a5: decode, legality gate, placement or swap, winner test, rewards / termination / auto-reset -------------
+struct LanePly {          // what one ply did to this lane's board
+  bool skip, frozen, ended, point_ok, swap_ok, reset;
+  float rew0, rew1;       // by player id; zero unless the ply ended the game
+};
+
+// a1-a5 for this lane's board (Fig. 2 "step"): decode, legality gate, placement or swap, winner test, rewards /
+// termination / auto-reset.  Every lane of the wavefront must call it (the flood's convergence test is a ballot).
+__device__ __forceinline__ LanePly lane_ply(B128& bk, B128& wt, Meta& m, int act, bool ok, int b, uint32_t seed, int auto_reset) {
+  LanePly out;
   const bool skip = act == -1 || !ok;
   const bool frozen = !skip && m.term;
   const bool live = !skip && !frozen;
-  const B128 board = set_of<0>();
-  const B128 E0 = b_andn(board, b_or(bk, wt));
+  const B128 E0 = b_andn(set_of<0>(), b_or(bk, wt));
   const bool want_point = live && act >= 0 && act < P;
   const B128 pbit = b_bit(want_point ? act : 0, want_point);
   const bool point_ok = want_point && b_any(b_and(E0, pbit));
@@ -461,82 +457,123 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
   const float r_other = won ? -1.f : (illegal_now ? 1.f : 0.f);
   m.illegal += illegal_now ? 1u : 0u;
   m.term = (m.term || ended) ? 1 : 0;
-  const bool reset = ended && a.auto_reset;
+  const bool reset = ended && auto_reset;
   if (reset) {   // Sec. 4.1: back to the initial state within the same ply
     m.episode += 1u;
     bk = B128{{0u, 0u, 0u, 0u}}; wt = bk;
     m.steps = 0; m.wtm = 0; m.term = 0;
-    m.bp = (int)(env_hash(a.seed, 1u, (uint32_t)b, m.episode) & 1u);
+    m.bp = (int)(env_hash(seed, 1u, (uint32_t)b, m.episode) & 1u);
   }
-  if (!skip) {
-    *(float2*)(a.rew + 2 * (size_t)b) = mover == 0 ? make_float2(r_mover, r_other) : make_float2(r_other, r_mover);
-    a.term[b] = (ended || frozen) ? 1 : 0;
-    a.meta[b] = pack_meta(m);
-    // a8: state store.  A placed stone changes one bit of one row word; a swap or a reset rewrites the board.
-    if (swap_ok || reset) {
-#pragma unroll
-      for (int r = 0; r < N; ++r) {
-        const int i = (N * r) >> 5, s = (N * r) & 31;
-        uint32_t kb = bk.w[i] >> s, kw = wt.w[i] >> s;
-        if (s + N > 32) { kb |= bk.w[i + 1] << (32 - s); kw |= wt.w[i + 1] << (32 - s); }
-        a.rows[(size_t)b * N + r] = (kb & FULL) | ((kw & FULL) << 16);
-      }
-    } else if (point_ok) {
-      const int pr = (int)(__umul24((uint32_t)act, 745u) >> 13);   // act / 11 for 0 <= act < 128
-      atomicOr(&a.rows[(size_t)b * N + pr], (1u << (act - pr * N)) << (wtm ? 16 : 0));
-    }
-  }
+  out.skip = skip; out.frozen = frozen; out.ended = ended; out.point_ok = point_ok; out.swap_ok = swap_ok; out.reset = reset;
+  out.rew0 = mover == 0 ? r_mover : r_other;
+  out.rew1 = mover == 0 ? r_other : r_mover;
+  return out;
+}
 
-  // ---- a6 / a7: legal mask [122] and observation [11][11][4] of the position after the ply ------------------------------
-  const bool swap = m.steps == 1;
-  B128 legal = b_andn(board, b_or(bk, wt));
-  if (swap) legal.w[3] |= 1u << (P - 96);   // the swap is action 121, the last one
+// the legal actions of the position as a 122-bit set (bit 121 = the swap)
+__device__ __forceinline__ B128 lane_legal(const B128& bk, const B128& wt, const Meta& m) {
+  B128 legal = b_andn(set_of<0>(), b_or(bk, wt));
+  if (m.steps == 1) legal.w[3] |= 1u << (P - 96);
+  return legal;
+}
+
+// a6 / a7: legal mask [122] and observation [11][11][4] of the 64 boards of the wavefront (nb real ones from board b0 on)
+__device__ __forceinline__ void lane_emit(const B128& bk, const B128& wt, const Meta& m, const B128& legal, bool ok, int lane, int b0, int nb,
+                                          uint8_t* mask, uint8_t* obs, uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, const uint32_t* lut4) {
   {
-    uint4* z = (uint4*)lds_obs[wib];
+    uint4* z = (uint4*)lds_obs;
 #pragma unroll
     for (int i = 0; i < (LANE_OBS_DW / 4 + 63) / 64; ++i)
       if (i * 64 + lane < LANE_OBS_DW / 4) z[i * 64 + lane] = make_uint4(0u, 0u, 0u, 0u);
-    if (lane < LANE_MASK_DW / 4) ((uint4*)lds_mask[wib])[lane] = make_uint4(0u, 0u, 0u, 0u);
+    if (lane < LANE_MASK_DW / 4) ((uint4*)lds_mask)[lane] = make_uint4(0u, 0u, 0u, 0u);
     static_assert(LANE_MASK_DW / 4 <= 64, "the mask stream is cleared by one store per lane");
   }
   wave_lds_fence();
-  if (a.mask && ok) {
-    const uint32_t head = (uint32_t)((uintptr_t)(a.mask + (size_t)b0 * A) & 15u);
-    stream_put<4, 1, 2>(lds_mask[wib], legal.w, head + (uint32_t)(A * lane));
+  if (mask && ok) {
+    const uint32_t head = (uint32_t)((uintptr_t)(mask + (size_t)b0 * A) & 15u);
+    stream_put<4, 1, 2>(lds_mask, legal.w, head + (uint32_t)(A * lane));
   }
-  if (a.obs && ok) {
+  if (obs && ok) {
     // 4 bits per cell: mover's stone, opponent's stone, Black to move, swap legal
     const B128 mine = m.wtm ? wt : bk, theirs = m.wtm ? bk : wt;
-    const uint32_t flags = (m.wtm ? 0u : 0x44444444u) | (swap ? 0x88888888u : 0u);
+    const uint32_t flags = (m.wtm ? 0u : 0x44444444u) | (m.steps == 1 ? 0x88888888u : 0u);
     uint32_t O[16];
 #pragma unroll
     for (int k = 0; k < 16; ++k) {
       const uint32_t mb = (mine.w[k >> 2] >> (8 * (k & 3))) & 255u, tb = (theirs.w[k >> 2] >> (8 * (k & 3))) & 255u;
       O[k] = lut4[mb] | (lut4[tb] << 1) | (k < 15 ? flags : (flags & 0xFu));
     }
-    const uint32_t head = (uint32_t)((uintptr_t)(a.obs + (size_t)b0 * OBS) & 15u);
-    stream_put<16, 1, 14>(lds_obs[wib], O, head + (uint32_t)(OBS * lane));
+    const uint32_t head = (uint32_t)((uintptr_t)(obs + (size_t)b0 * OBS) & 15u);
+    stream_put<16, 1, 14>(lds_obs, O, head + (uint32_t)(OBS * lane));
   }
   wave_lds_fence();
-  if (a.mask) emit_bytes<LANE_MASK_ROUNDS>(lds_mask[wib], lut, a.mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
-  if (a.obs) emit_bytes<LANE_OBS_ROUNDS>(lds_obs[wib], lut, a.obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
+  if (mask) emit_bytes<LANE_MASK_ROUNDS>(lds_mask, lut, mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
+  if (obs) emit_bytes<LANE_OBS_ROUNDS>(lds_obs, lut, obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
+  wave_lds_fence();
+}
 
-  if (SAMPLE) {   // the next uniform random legal action: the k-th set bit of the legal set, k = hash mod count
-    const bool wait = a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
-    const uint32_t c0 = __popc(legal.w[0]), c1 = __popc(legal.w[1]), c2 = __popc(legal.w[2]), c3 = __popc(legal.w[3]);
-    const uint32_t total = c0 + c1 + c2 + c3;
-    uint32_t k = env_hash(a.sample_seed, 0u, (uint32_t)b, a.sample_t) % (total ? total : 1u);
-    uint32_t w = legal.w[0], base = 0u;
-    if (k >= c0) { k -= c0; w = legal.w[1]; base = 32u;
-      if (k >= c1) { k -= c1; w = legal.w[2]; base = 64u;
-        if (k >= c2) { k -= c2; w = legal.w[3]; base = 96u; } } }
-    uint32_t pos = 0u;
+// the uniform random legal action of this lane's board: the k-th set bit of the legal set, k = hash mod count
+__device__ __forceinline__ int lane_draw(const B128& legal, uint32_t seed, uint32_t b, uint32_t t, bool wait) {
+  const uint32_t c0 = __popc(legal.w[0]), c1 = __popc(legal.w[1]), c2 = __popc(legal.w[2]), c3 = __popc(legal.w[3]);
+  const uint32_t total = c0 + c1 + c2 + c3;
+  uint32_t k = env_hash(seed, 0u, b, t) % (total ? total : 1u);
+  uint32_t w = legal.w[0], base = 0u;
+  if (k >= c0) { k -= c0; w = legal.w[1]; base = 32u;
+    if (k >= c1) { k -= c1; w = legal.w[2]; base = 64u;
+      if (k >= c2) { k -= c2; w = legal.w[3]; base = 96u; } } }
+  uint32_t pos = 0u;
 #pragma unroll
-    for (int width = 16; width >= 1; width >>= 1) {
-      const uint32_t c = __popc(w & ((1u << width) - 1u));
-      if (k >= c) { k -= c; w >>= width; pos += width; }
+  for (int width = 16; width >= 1; width >>= 1) {
+    const uint32_t c = __popc(w & ((1u << width) - 1u));
+    if (k >= c) { k -= c; w >>= width; pos += width; }
+  }
+  return wait ? -1 : (total == 0u ? 0 : (int)(base + pos));
+}
+
+template <bool SAMPLE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(StepArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ uint32_t lut4[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][LANE_OBS_DW];
+  __shared__ __align__(16) uint32_t lds_mask[kWavesPerBlock][LANE_MASK_DW];
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int b0 = wave * 64;                 // first board of the wavefront
+  const int b = b0 + lane;
+  const bool ok = b < a.B;
+  // state: 11 row words, the scalar record, the action
+  uint32_t row[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) row[r] = ok ? a.rows[(size_t)b * N + r] : 0u;
+  const uint4 mv = ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u);
+  const int act = ok ? a.actions[b] : -1;
+  fill_spread4_table(lut4);
+  fill_spread_table(lut);                   // ends with the block's only barrier
+  if (b0 >= a.B) return;
+  const int nb = a.B - b0 < 64 ? a.B - b0 : 64;
+  Meta m = unpack_meta(mv);
+  B128 bk, wt;
+  rows_to_sets(row, bk, wt);
+  const int wtm = m.wtm;
+  const LanePly ply = lane_ply(bk, wt, m, act, ok, b, a.seed, a.auto_reset);
+  if (!ply.skip) {
+    *(float2*)(a.rew + 2 * (size_t)b) = make_float2(ply.rew0, ply.rew1);
+    a.term[b] = (ply.ended || ply.frozen) ? 1 : 0;
+    a.meta[b] = pack_meta(m);
+    // a8: state store.  A placed stone changes one bit of one row word; a swap or a reset rewrites the board.
+    if (ply.swap_ok || ply.reset) {
+      store_sets_as_rows(a.rows + (size_t)b * N, bk, wt);
+    } else if (ply.point_ok) {
+      const int pr = (int)(__umul24((uint32_t)act, 745u) >> 13);   // act / 11 for 0 <= act < 128
+      atomicOr(&a.rows[(size_t)b * N + pr], (1u << (act - pr * N)) << (wtm ? 16 : 0));
     }
-    if (ok) a.next_actions[b] = wait ? -1 : (total == 0u ? 0 : (int)(base + pos));
+  }
+  const B128 legal = lane_legal(bk, wt, m);
+  lane_emit(bk, wt, m, legal, ok, lane, b0, nb, a.mask, a.obs, lds_mask[wib], lds_obs[wib], lut, lut4);
+  if (SAMPLE) {
+    const bool wait = a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
+    const int next = lane_draw(legal, a.sample_seed, (uint32_t)b, a.sample_t, wait);
+    if (ok) a.next_actions[b] = next;
   }
 }
 
@@ -590,6 +627,53 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_kernel(Rollou
   }
   if (L.valid) a.rows[(size_t)L.b * N + L.r] = bk | (wt << 16);
   if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+}
+
+// the same with a board per lane (very large batches): state of 64 boards in the registers of one wavefront
+__global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_lane_kernel(RolloutArgs a) {
+  __shared__ uint2 lut[256];
+  __shared__ uint32_t lut4[256];
+  __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][LANE_OBS_DW];
+  __shared__ __align__(16) uint32_t lds_mask[kWavesPerBlock][LANE_MASK_DW];
+  fill_spread4_table(lut4);
+  fill_spread_table(lut);
+  const int wib = wave_in_block(), lane = threadIdx.x & 63;
+  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int b0 = wave * 64;
+  if (b0 >= a.B) return;
+  const int b = b0 + lane;
+  const bool ok = b < a.B;
+  const int nb = a.B - b0 < 64 ? a.B - b0 : 64;
+  uint32_t row[N];
+#pragma unroll
+  for (int r = 0; r < N; ++r) row[r] = ok ? a.rows[(size_t)b * N + r] : 0u;
+  Meta m = unpack_meta(ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u));
+  const int64_t start = (ok && a.start_t) ? (int64_t)a.start_t[b] : INT64_MIN;
+  B128 bk, wt;
+  rows_to_sets(row, bk, wt);
+  B128 legal = lane_legal(bk, wt, m);
+  int slice = 0;
+  for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
+    const uint32_t t = a.t0 + (uint32_t)i;
+    const bool wait = (int64_t)t < start;
+    const int act = ok ? lane_draw(legal, a.seed, (uint32_t)b, t, wait) : -1;
+    const LanePly ply = lane_ply(bk, wt, m, act, ok, b, a.seed_env, a.auto_reset);
+    legal = lane_legal(bk, wt, m);
+    const size_t sb = (size_t)slice * a.B;
+    if (ok) {
+      const size_t e = sb + b;
+      if (a.actions) a.actions[e] = act;
+      if (a.rew) *(float2*)(a.rew + 2 * e) = ply.skip ? make_float2(0.f, 0.f) : make_float2(ply.rew0, ply.rew1);
+      if (a.term) a.term[e] = (uint8_t)((!ply.skip && (ply.ended || ply.frozen)) ? 1 : 0);
+    }
+    lane_emit(bk, wt, m, legal, ok, lane, b0, nb, a.mask ? a.mask + sb * A : nullptr, a.obs ? a.obs + sb * OBS : nullptr, lds_mask[wib], lds_obs[wib], lut,
+              lut4);
+    slice = slice + 1 == a.slices ? 0 : slice + 1;
+  }
+  if (ok) {
+    store_sets_as_rows(a.rows + (size_t)b * N, bk, wt);
+    a.meta[b] = pack_meta(m);
+  }
 }
 
 __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uint32_t* rows, const uint4* meta, int B, uint8_t* mask, uint8_t* obs) {
@@ -843,7 +927,10 @@ int pgxhex_rollout(pgxhex_t h, int32_t steps, int32_t slices, uint32_t seed, uin
   a.rows = h->rows; a.meta = h->meta; a.B = h->B; a.seed_env = h->seed; a.auto_reset = h->auto_reset;
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
-  hipLaunchKernelGGL(hex_rollout_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
+  if (board_per_lane(h))
+    hipLaunchKernelGGL(hex_rollout_lane_kernel, dim3((unsigned)((h->B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock))), dim3(64 * kWavesPerBlock), 0,
+                       h->stream, a);
+  else hipLaunchKernelGGL(hex_rollout_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXHEX_OK;
 }

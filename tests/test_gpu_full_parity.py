@@ -51,6 +51,12 @@ def test_every_environment_every_ply_with_superko_through_the_rollout_kernel(con
     assert n == EXPECTED[("go", config)]
 
 
+def test_every_environment_every_ply_hex_rollout_with_a_board_per_lane():
+    """The Hex rollout kernel in the board-per-lane mapping, 8 plies per launch, every ply in its own slice."""
+    n = full_parity.run(full_parity.Args(game="hex", config=1, rollout=8, mapping=2))
+    assert n == EXPECTED[("hex", 1)]
+
+
 @pytest.mark.parametrize("game,config", [("go", 1), ("go", 3), ("hex", 1)])
 def test_every_environment_every_ply_through_the_rollout_kernel(game, config):
     """The rollout kernel, 8 plies per launch with every ply recorded in its own slice."""

@@ -314,11 +314,13 @@ def alloc_traj(S, B):
                 obs=torch.empty((S, B, OBS), dtype=torch.uint8, device="cuda"))
 
 
+@pytest.mark.parametrize("mapping", [1, 2])
 @pytest.mark.parametrize("B,auto_reset,stagger", [(131, True, False), (64, False, False), (77, True, True)])
-def test_rollout_kernel_records_the_trajectory(B, auto_reset, stagger):
-    """One launch of T plies against ply-by-ply oracle stepping: every slice of the recorded trajectory is compared."""
+def test_rollout_kernel_records_the_trajectory(B, auto_reset, stagger, mapping):
+    """One launch of T plies against ply-by-ply oracle stepping: every slice of the recorded trajectory is compared
+    (both mappings: a board row per lane, a board per lane)."""
     seed, T = 31, 140
-    p = HexPair(B, seed=seed, auto_reset=auto_reset, bind=False)
+    p = HexPair(B, seed=seed, auto_reset=auto_reset, bind=False, mapping=mapping)
     start = (np.arange(B) % 23).astype(np.int32) if stagger else None
     tr = alloc_traj(T, B)
     p.env.rollout(T, seed, 0, start_t=None if start is None else torch.as_tensor(start, device="cuda"), slices=T, **tr)
