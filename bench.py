@@ -468,7 +468,7 @@ def bench_go(args, cfg):
                           "note": "pgxgo_rollout: the same plies and outputs (in place) with rollout_len plies per launch; not the headline value"}
     if not args.no_cpu_baseline:
         n_threads = max(1, min(16, os.cpu_count() or 1))
-        per = max(1, min(64, B // n_threads))
+        per = max(1, min(64 if N == 19 else 256, B // n_threads))    # enough work per call that the C code, not the interpreter, is timed
         cpu_plies = 1500 if cfg.auto_reset else K
         single, multi, reps = cpu_baseline(cfg, pre + Wm, cpu_plies, n_threads, per, superko=args.superko)
         out["cpu_baseline"] = {"value": multi, "unit": "env steps/s", "cores": n_threads, "kind": "oracle",
@@ -578,7 +578,7 @@ def bench_hex(args, cfg):
         out["roofline"]["binding"] = bound_statement(kern_ms * 1e3, floor_us, fill["in_place_ms"] * 1e3, math.ceil(B / 5) / 1024.0)
     if not args.no_cpu_baseline:
         n_threads = max(1, min(16, os.cpu_count() or 1))
-        per = max(1, min(64, B // n_threads))
+        per = max(1, min(1024, B // n_threads))                      # enough work per call that the C code, not the interpreter, is timed
         cpu_plies = 1500 if cfg.auto_reset else K
         single, multi, reps = cpu_baseline(cfg, pre + Wm, cpu_plies, n_threads, per)
         out["cpu_baseline"] = {"value": multi, "unit": "env steps/s", "cores": n_threads, "kind": "oracle",
