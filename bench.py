@@ -629,6 +629,19 @@ def ceilings(args, cfg):
         res["rollout_ms_per_ply_by_slices"][str(S)] = timed(lambda i: env.rollout(Lr, seed, pre + 20 + i * Lr, start_t=st.start, slices=S, **bufs),
                                                             max(1, K // Lr)) / Lr
         del bufs, env
+    # the search-facing calls: B entries out of a pool of 2B games in the same regime, sources and destinations scattered over the pool
+    pool = pg.GoEnv(2 * B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=True)
+    pool.rollout(pre + 20, seed, 0, slices=1)
+    g = torch.Generator().manual_seed(seed)
+    perm = torch.randperm(2 * B, generator=g).to(torch.int32).cuda()
+    src, dst = perm[:B].contiguous(), perm[B:].contiguous()
+    acts = pool.random_actions(seed, pre + 20)[src.long()].contiguous()
+    m, o = st.mask, st.obs
+    rew, term = torch.empty(B, 2, dtype=torch.float32, device="cuda"), torch.empty(B, dtype=torch.uint8, device="cuda")
+    res["slots"] = {"pool": 2 * B, "entries": B,
+                    "step_slots_ms": timed(lambda i: pool.step_slots(src, acts, dst, mask=m, obs=o, rewards=rew, terminated=term), 200),
+                    "step_slots_mask_only_ms": timed(lambda i: pool.step_slots(src, acts, dst, mask=m, rewards=rew, terminated=term), 200),
+                    "copy_slots_ms": timed(lambda i: pool.copy_slots(src, dst), 200)}
     print(json.dumps(res))
 
 

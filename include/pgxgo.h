@@ -191,8 +191,8 @@ int pgxgo_set_boards_per_wavefront(pgxgo_t h, int32_t boards);
  *   mode 1: the rule is looked at only when the move is played (same consequence for the offender), while the mask
  *           keeps showing the simple-ko set.
  *   mode 0 (table_dev ignored): off.
- * Positions are compared through their stone counts and 45 bits of a Zobrist key, kept in a per-game table inside
- * table_dev.  pgxgo_superko_bytes: bytes of device memory the tables need (0 for invalid arguments); 256-byte aligned.
+ * Positions are compared through two 32-bit Zobrist keys, one per colour (64 bits in all; probe chains are chosen by
+ * the stone counts), kept in a per-game table inside table_dev.  pgxgo_superko_bytes: bytes of device memory the tables need (0 for invalid arguments); 256-byte aligned.
  * pgxgo_enable_superko switches the rule on with a caller-owned buffer that must outlive the handle.  The positions
  * known from then on are the ones the state still carries (the 8 history positions and the current one); the same
  * holds after pgxgo_import_state.  Needs max_steps <= 2*N*N.  Every entry point honours the rule: pgxgo_step /
