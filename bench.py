@@ -211,6 +211,8 @@ def main():
     ap.add_argument("--rollout-slices", type=int, default=1, help="trajectory slices the rollout writes to (1 = overwrite one set of buffers)")
     ap.add_argument("--superko", type=int, default=0, choices=[0, 1, 2], help="Go only: positional superko, 2 = honoured by the legal mask (the rule "
                                                                               "proper), 1 = enforced when the move is played (not the headline metric)")
+    ap.add_argument("--line-padded", action="store_true", help="Go only: mask and observation pitches rounded up to 128-byte lines (not the "
+                    "paper's dense tensors, hence not the headline: the layout for outputs that have to reach DRAM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-obs", action="store_true", help="do not emit the observation (not the headline metric)")
     ap.add_argument("--ceilings", action="store_true", help="print the reference measurements of this configuration instead of the benchmark line")
@@ -243,19 +245,25 @@ def main():
     return bench_go(args, cfg)
 
 
-def go_rollout_buffers(torch, S, B, P, with_obs):
+def go_pitches(N, line_padded):
+    """(mask pitch, observation pitch) in bytes: dense, or rounded up to 128-byte lines."""
+    P = N * N
+    return ((P + 1 + 127) // 128 * 128, (P * 17 + 127) // 128 * 128) if line_padded else (P + 1, P * 17)
+
+
+def go_rollout_buffers(torch, S, B, pitches, with_obs):
     return dict(actions=torch.empty((S, B), dtype=torch.int32, device="cuda"),
                 rewards=torch.empty((S, B, 2), dtype=torch.float32, device="cuda"),
                 terminated=torch.empty((S, B), dtype=torch.uint8, device="cuda"),
-                mask=torch.empty((S, B, P + 1), dtype=torch.uint8, device="cuda"),
-                obs=torch.empty((S, B, P * 17), dtype=torch.uint8, device="cuda") if with_obs else None)
+                mask=torch.empty((S, B, pitches[0]), dtype=torch.uint8, device="cuda"),
+                obs=torch.empty((S, B, pitches[1]), dtype=torch.uint8, device="cuda") if with_obs else None)
 
 
 class GoStepper:
     """The one-launch-per-ply path on a GoEnv: pre-roll through the rollout kernel, then step_sample (fused) or
     step + random_actions (separate) with launch index t; acts[t & 1] holds the actions of launch t."""
 
-    def __init__(self, cfg, B, with_obs, fused=True, superko=False):
+    def __init__(self, cfg, B, with_obs, fused=True, superko=False, line_padded=False):
         import torch
 
         import paper_2303_17503_amd as pg
@@ -263,7 +271,7 @@ class GoStepper:
 
         self.torch, self.cfg, self.B, self.fused = torch, cfg, B, fused
         N = cfg.board_size
-        self.env = pg.GoEnv(B, N, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
+        self.env = pg.GoEnv(B, N, seed=cfg.seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, line_padded=line_padded)
         if superko:
             self.env.enable_superko(int(superko))
         ids = None if B == cfg.batch else list(range(B))
@@ -319,7 +327,8 @@ def bench_go(args, cfg):
     with_obs = not args.no_obs
     P = N * N
     pre = cfg.warmup_max + cfg.preroll     # plies before the timed path starts: configuration 4's own warm-up, then the pre-roll
-    out_bytes = B * ((P + 1) + (P * 17 if with_obs else 0))
+    pitches = go_pitches(N, args.line_padded)
+    out_bytes = B * (pitches[0] + (pitches[1] if with_obs else 0))
     S_rot = rotation_slices(out_bytes)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     dram = None
@@ -328,13 +337,13 @@ def bench_go(args, cfg):
     if args.mode == "rollout":
         S, Lr = args.rollout_slices, args.rollout_len
         assert K % Lr == 0, "--steps must be a multiple of --rollout-len"
-        env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
+        env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, line_padded=args.line_padded)
         if args.superko:
             env.enable_superko(int(args.superko))
         import workloads
         start = workloads.start_times(cfg)
         start_dev = None if start is None else torch.as_tensor(start, device="cuda")
-        bufs = go_rollout_buffers(torch, S, B, P, with_obs)
+        bufs = go_rollout_buffers(torch, S, B, pitches, with_obs)
         env.rollout(pre + Wm, seed, 0, start_t=start_dev, slices=S, **bufs)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -347,12 +356,12 @@ def bench_go(args, cfg):
         kern_ms = ev0.elapsed_time(ev1) / K       # per ply: the launch covers rollout_len plies
         kname = "go_rollout_kernel<%d>" % N
         if S == 1:
-            bufs_r = go_rollout_buffers(torch, S_rot, B, P, with_obs)
+            bufs_r = go_rollout_buffers(torch, S_rot, B, pitches, with_obs)
             ms = timed(lambda i: env.rollout(Lr, seed, pre + Wm + K + i * Lr, start_t=start_dev, slices=S_rot, **bufs_r), max(1, K // Lr)) / Lr
             dram = {"slices": S_rot, "kernel_ms": ms}
             del bufs_r
     else:
-        st = GoStepper(cfg, B, with_obs, fused=(args.mode == "fused"), superko=args.superko)
+        st = GoStepper(cfg, B, with_obs, fused=(args.mode == "fused"), superko=args.superko, line_padded=args.line_padded)
         st.preroll(pre)
         st.run(Wm)
         torch.cuda.synchronize()
@@ -399,7 +408,7 @@ def bench_go(args, cfg):
     gap_us = launch_gap_us()
     copy_gbs = device_copy_gbs(out_bytes)
     pmc_file = os.path.join("profiles", f"{'go_rollout_kernel' if args.mode == 'rollout' else 'go_step_kernel'}_{cfg.name}.txt")
-    traffic = read_traffic(os.path.join(ROOT, pmc_file)) if with_obs and args.mode != "separate" and not args.superko else None
+    traffic = read_traffic(os.path.join(ROOT, pmc_file)) if with_obs and args.mode != "separate" and not args.superko and not args.line_padded else None
     if dram is not None:
         a = bytes_ply * B / (dram["kernel_ms"] * 1e-3) / 1e9
         dram.update({"achieved": a, "frac": a / HBM_PEAK_GBS, "frac_of_fill": fill["rotating_ms"] / dram["kernel_ms"],
@@ -422,6 +431,8 @@ def bench_go(args, cfg):
         "data": "synthetic",
         "config": {"workload": cfg.name, "board_size": N, "batch": B, "seed": seed, "auto_reset": cfg.auto_reset,
                    "observation": with_obs, "mode": args.mode, "superko": int(args.superko), "komi": cfg.komi_x2 / 2,
+                   "layout": f"line-padded (mask pitch {pitches[0]}, observation pitch {pitches[1]}; pad bytes written as zeros)" if args.line_padded
+                             else "dense (the paper's tensor shapes)",
                    "pre_roll_plies": pre, "timed_ply_window": window,
                    "window_note": f"launch indices since init; plies 0..{pre - 1} are an untimed pre-roll through pgxgo_rollout (boards dense, games out "
                                   f"of step), then {Wm} untimed launches of the timed path",
@@ -443,13 +454,13 @@ def bench_go(args, cfg):
     if args.mode != "rollout":
         # the ply of ONE wavefront of the same kernel (W boards), launch gap included: the latency floor of a launch
         W = pg.lib().pgxgo_boards_per_wavefront(N)
-        tiny = GoStepper(cfg, W, with_obs, fused=(args.mode == "fused"))
+        tiny = GoStepper(cfg, W, with_obs, fused=(args.mode == "fused"), line_padded=args.line_padded)
         tiny.env.set_boards_per_wavefront(W)
         tiny.preroll(min(pre, 60)); tiny.run(20)
         floor_us = timed(lambda i: tiny.step_once(), 200) * 1e3
         wb = st.env.set_boards_per_wavefront(0)
         out["roofline"]["binding"] = bound_statement(kern_ms * 1e3, floor_us, fill["in_place_ms"] * 1e3, math.ceil(B / wb) / 1024.0)
-    if args.mode == "fused" and not args.superko and K >= args.rollout_len:
+    if args.mode == "fused" and not args.superko and not args.line_padded and K >= args.rollout_len:
         # for information: the same workload and ply window through the rollout kernel (rollout_len plies per launch, state in registers)
         Lr = args.rollout_len
         Kr = K // Lr * Lr
@@ -601,12 +612,13 @@ def ceilings(args, cfg):
     P = N * N
     with_obs = not args.no_obs
     pre = cfg.warmup_max + cfg.preroll
-    out_bytes = B * ((P + 1) + (P * 17 if with_obs else 0))
+    pitches = go_pitches(N, args.line_padded)
+    out_bytes = B * (pitches[0] + (pitches[1] if with_obs else 0))
     S_rot = rotation_slices(out_bytes)
     K = min(args.steps, 500)
-    res = {"workload": cfg.name, "observation": with_obs, "output_bytes_per_ply": out_bytes, "pre_roll_plies": pre, "plies_timed": K,
+    res = {"workload": cfg.name, "observation": with_obs, "layout": "line-padded" if args.line_padded else "dense", "output_bytes_per_ply": out_bytes, "pre_roll_plies": pre, "plies_timed": K,
            "launch_gap_us": launch_gap_us(), "fill": fill_ceiling(out_bytes, S_rot), "device_copy_gbs": device_copy_gbs(out_bytes)}
-    st = GoStepper(cfg, B, with_obs)
+    st = GoStepper(cfg, B, with_obs, line_padded=args.line_padded)
     st.preroll(pre); st.run(20)
     res["emit_only_ms"] = timed(lambda i: st.env.emit(st.mask, st.obs), 200)
     res["step_fused_in_place_ms"] = timed(lambda i: st.step_once(), K)
@@ -623,14 +635,14 @@ def ceilings(args, cfg):
     for S in (1, 2, 4, 8, 16):
         if S * out_bytes > (12 << 30):
             break
-        env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset)
-        bufs = go_rollout_buffers(torch, S, B, P, with_obs)
+        env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, line_padded=args.line_padded)
+        bufs = go_rollout_buffers(torch, S, B, pitches, with_obs)
         env.rollout(pre + 20, seed, 0, start_t=st.start, slices=S, **bufs)
         res["rollout_ms_per_ply_by_slices"][str(S)] = timed(lambda i: env.rollout(Lr, seed, pre + 20 + i * Lr, start_t=st.start, slices=S, **bufs),
                                                             max(1, K // Lr)) / Lr
         del bufs, env
     # the search-facing calls: B entries out of a pool of 2B games in the same regime, sources and destinations scattered over the pool
-    pool = pg.GoEnv(2 * B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=True)
+    pool = pg.GoEnv(2 * B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=True, line_padded=args.line_padded)
     pool.rollout(pre + 20, seed, 0, slices=1)
     g = torch.Generator().manual_seed(seed)
     perm = torch.randperm(2 * B, generator=g).to(torch.int32).cuda()

@@ -50,6 +50,11 @@ typedef struct {
   int32_t auto_reset; /* 1: a finished game is re-initialised within the same step call (Sec. 4.1) */
   int32_t obs_pitch;  /* bytes between consecutive environments in observation buffers; 0 = N*N*17 (tight) */
   int32_t mask_pitch; /* bytes between consecutive environments in legal-mask buffers; 0 = N*N+1 (tight) */
+  /* Pad bytes between the environments' records are left untouched, with one exception: the line-padded pitches
+   * (N*N*17 and N*N+1 rounded up to the next multiple of 128: 6144 / 384 at 19x19, 1408 / 128 at 9x9), where they are
+   * written as zeros together with the record.  With both pitches dense or line-padded a wavefront writes its boards
+   * as one run of bytes; with line-padded pitches and 128-byte aligned buffers that run consists of whole 128-byte
+   * lines only, which is the fastest layout for outputs that have to reach DRAM (every ply into fresh memory). */
   void* stream;       /* hipStream_t of the caller; NULL = default stream */
 } pgxgo_opts;
 

@@ -85,11 +85,17 @@ class GoEnv:
     """`batch` Go games on one GPU (paper Fig. 2 API)."""
 
     def __init__(self, batch, board_size, seed=0, komi_x2=15, max_steps=0, auto_reset=False, obs_pitch=0, mask_pitch=0,
-                 device="cuda:0", static_state=False):
+                 device="cuda:0", static_state=False, line_padded=False):
+        """line_padded: use the pitches at which every environment's mask and observation start on a 128-byte line
+        (N*N+1 and N*N*17 rounded up to multiples of 128; the pad bytes are written as zeros).  Outputs that have to
+        reach DRAM, such as recorded trajectories, are written faster in this layout; mask_view / obs_view give the
+        [B][N*N+1] and [B][N][N][17] views."""
         L = lib()
         self.B, self.N = int(batch), int(board_size)
         self.P = self.N * self.N
         self.A = self.P + 1
+        if line_padded:
+            obs_pitch, mask_pitch = (self.P * 17 + 127) // 128 * 128, (self.A + 127) // 128 * 128
         self.device = torch.device(device)
         nbytes = L.pgxgo_state_bytes(self.B, self.N)
         if nbytes == 0:
@@ -126,8 +132,8 @@ class GoEnv:
         return t[:, : self.A]
 
     def obs_view(self, t):
-        return t[:, : self.P * 17].reshape(self.B, self.N, self.N, 17) if self.obs_pitch == self.P * 17 else \
-            t[:, : self.P * 17].contiguous().reshape(self.B, self.N, self.N, 17)
+        """[B][N][N][17] view of an observation buffer (strided when the pitch is padded; no copy)."""
+        return t.as_strided((t.shape[0], self.N, self.N, 17), (self.obs_pitch, self.N * 17, 17, 1), t.storage_offset())
 
     def bind_outputs(self, mask=None, obs=None, rewards=None, terminated=None):
         if mask is not None: _need(mask, torch.uint8, (self.B, self.mask_pitch), "mask")

@@ -81,10 +81,10 @@ struct Geo {
   static constexpr int ROWBITS = N * 17;      // observation bits contributed by one row
   static constexpr int NR = (ROWBITS + 31) / 32;       // dwords of one row's bit string
   static constexpr int NI = ROWBITS / 32 - 1;          // dwords 1..NI of the shifted string are never shared with another row
-  static constexpr int OBS_DW = ((OBS + 15 + 31) / 32 + 3) / 4 * 4;   // LDS dwords of one board's bit stream (+ up to 15 lead bits)
+  static constexpr int OBS_PAD = (OBS + 127) / 128 * 128;   // the pitches at which every board starts on a 128-byte line
+  static constexpr int A_PAD = (A + 127) / 128 * 128;
+  static constexpr int OBS_DW = ((OBS_PAD + 15 + 31) / 32 + 3) / 4 * 4;   // LDS dwords of one board's bit stream (+ up to 15 lead bits)
   static constexpr int MASK_DW = ((A + 15 + 31) / 32 + 3) / 4 * 4;
-  static constexpr int OBS_ROUNDS = (OBS / 16 + 63) / 64;   // 64-lane rounds of 16-byte groups per board (whole groups <= OBS/16)
-  static constexpr int MASK_ROUNDS = (A / 16 + 63) / 64;
   static constexpr size_t row_bytes = (size_t)REC * 4;
   // lanes holding the rows of board slot j
   static constexpr uint64_t seg(int j) { return ((1ull << N) - 1ull) << (j * STRIDE + 1); }
@@ -248,14 +248,16 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
   return E & ~kobit & dilate(support);
 }
 
-// Legal mask bytes [N*N+1] of every board of the wavefront.  With the tight pitch the boards of a wavefront are
-// one contiguous run of bytes and are staged and written as one stream; otherwise board by board.
+// Legal mask bytes [N*N+1] of every board of the wavefront.  TIGHT: the pitch is the dense one (N*N+1) or the
+// line-padded one (A_PAD); the boards of a wavefront are then one contiguous run of bytes, pad bytes included, and
+// are staged and written as one stream (the pad bytes as zeros); otherwise board by board, pad bytes untouched.
 template <int N, bool TIGHT, bool NT = false>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
                                           uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
-  static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
-  constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1
+  static_assert(G::W * G::MASK_DW <= 64 && (15 + G::W * G::A_PAD + 31) / 32 <= 64, "mask staging is cleared by one store per lane");
+  constexpr bool tight = TIGHT;   // the caller guarantees mask_pitch == N*N+1 or A_PAD
+  const uint32_t stride = (uint32_t)mask_pitch;
   const int b0 = wave * wb;
   const int nb = B - b0 < wb ? B - b0 : wb;   // boards of this wavefront
   lds_mask[L.lane] = 0u;
@@ -263,7 +265,7 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   if (L.valid) {
     uint32_t* reg;
     uint32_t head;
-    if constexpr (tight) { head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * G::A) & 15u) + (uint32_t)(L.j * G::A); reg = lds_mask; }
+    if constexpr (tight) { head = (uint32_t)((uintptr_t)(mask + (int64_t)b0 * mask_pitch) & 15u) + __umul24((uint32_t)L.j, stride); reg = lds_mask; }
     else { head = (uint32_t)((uintptr_t)(mask + (int64_t)L.b * mask_pitch) & 15u); reg = lds_mask + L.j * G::MASK_DW; }
     const uint32_t o = head + (uint32_t)(N * L.r), q = o >> 5, s = o & 31u;
     atomicOr(&reg[q], legal << s);
@@ -272,11 +274,11 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::A / 16 + 63) / 64, NT>(lds_mask, lut, mask + (int64_t)b0 * G::A, (uint32_t)(nb * G::A), L.lane);
+    emit_bytes<G::W * G::A_PAD, NT>(lds_mask, lut, mask + (int64_t)b0 * mask_pitch, (uint32_t)nb * stride, L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::MASK_ROUNDS, NT>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
+      if (jj < nb) emit_bytes<G::A, NT>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
   }
   wave_lds_fence();
 }
@@ -286,8 +288,9 @@ template <int N, bool TIGHT, bool NT = false>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
                                          int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
-  static_assert((15 + G::W * G::OBS + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
-  constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17
+  static_assert((15 + G::W * G::OBS_PAD + 31) / 32 <= G::W * G::OBS_DW, "one stream for all boards fits the staging area");
+  constexpr bool tight = TIGHT;   // the caller guarantees obs_pitch == N*N*17 or OBS_PAD (see emit_mask)
+  const uint32_t stride = (uint32_t)obs_pitch;
   const int b0 = wave * wb;
   const int nb = B - b0 < wb ? B - b0 : wb;
   // 17 bits per point: the point's history halfword seen by the mover (pairs swapped when White moves),
@@ -320,7 +323,7 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   if (L.valid) {
     uint32_t* reg;
     uint32_t head;
-    if constexpr (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * G::OBS) & 15u) + (uint32_t)(L.j * G::OBS); reg = lds_obs; }
+    if constexpr (tight) { head = (uint32_t)((uintptr_t)(obs + (int64_t)b0 * obs_pitch) & 15u) + __umul24((uint32_t)L.j, stride); reg = lds_obs; }
     else { head = (uint32_t)((uintptr_t)(obs + (int64_t)L.b * obs_pitch) & 15u); reg = lds_obs + L.j * G::OBS_DW; }
     // The row's string goes to bit offset o of the stream.  Written as a left shift by u = 1..32 from dword (o-u)/32
     // on, every shifted dword is one funnel shift of two neighbours of S (a shift by 0 would need a special case):
@@ -343,21 +346,21 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<(G::W * G::OBS / 16 + 63) / 64, NT>(lds_obs, lut, obs + (int64_t)b0 * G::OBS, (uint32_t)(nb * G::OBS), L.lane);
+    emit_bytes<G::W * G::OBS_PAD, NT>(lds_obs, lut, obs + (int64_t)b0 * obs_pitch, (uint32_t)nb * stride, L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::OBS_ROUNDS, NT>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
+      if (jj < nb) emit_bytes<G::OBS, NT>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
   }
   wave_lds_fence();
 }
 
-template <int N, bool TIGHT>
+template <int N, bool TIGHT, bool NT = false>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
                                              uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
-  if (mask) emit_mask<N, TIGHT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
-  if (obs) emit_obs<N, TIGHT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
+  if (mask) emit_mask<N, TIGHT, NT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
+  if (obs) emit_obs<N, TIGHT, NT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1629,9 +1632,13 @@ int auto_boards_per_wavefront(int B) {
   return want < 1 ? 1 : (want > Geo<N>::W ? Geo<N>::W : want);
 }
 
-// both output pitches are the tight ones: the kernels may treat a wavefront's boards as one run of bytes
+// both output pitches are the dense or the line-padded ones: the kernels treat a wavefront's boards as one run of bytes
+// (with the line-padded pitch the pad bytes belong to that run and are written as zeros)
 template <int N>
-bool tight_pitches(const pgxgo_ctx* h) { return h->mask_pitch == Geo<N>::A && h->obs_pitch == Geo<N>::OBS; }
+bool tight_pitches(const pgxgo_ctx* h) {
+  using G = Geo<N>;
+  return (h->mask_pitch == G::A || h->mask_pitch == G::A_PAD) && (h->obs_pitch == G::OBS || h->obs_pitch == G::OBS_PAD);
+}
 
 template <int N, bool TIGHT, bool SK>
 void launch_emit_as(pgxgo_ctx* h, uint8_t* mask, uint8_t* obs) {

@@ -46,8 +46,6 @@ constexpr uint32_t FULL = (1u << N) - 1u;
 constexpr int kWavesPerBlock = 4;           // wavefronts never synchronise with each other after the table is filled
 constexpr int OBS_DW = ((15 + W * OBS + 31) / 32 + 3) / 4 * 4;   // LDS dwords of a wavefront's observation bit stream
 constexpr int MASK_DW = 64;                                      // the mask stream is cleared by one store per lane
-constexpr int OBS_ROUNDS = (W * OBS / 16 + 63) / 64;
-constexpr int MASK_ROUNDS = (W * A / 16 + 63) / 64;
 static_assert(A == PGXHEX_ACTIONS && OBS == PGXHEX_OBS_BYTES, "header constants");
 static_assert((15 + W * A + 31) / 32 <= MASK_DW, "mask stream fits its staging area");
 static_assert(N <= 16, "a row holds both colours in one dword");
@@ -123,7 +121,7 @@ __device__ __forceinline__ void emit_outputs(const Lane& L, uint32_t bk, uint32_
       if (L.r == 0 && swap) { const uint32_t o2 = head + P; atomicOr(&lds_mask[o2 >> 5], 1u << (o2 & 31u)); }
     }
     wave_lds_fence();
-    emit_bytes<MASK_ROUNDS>(lds_mask, lut, mask + (int64_t)b0 * A, (uint32_t)(nb * A), L.lane);
+    emit_bytes<W * A>(lds_mask, lut, mask + (int64_t)b0 * A, (uint32_t)(nb * A), L.lane);
     wave_lds_fence();
   }
   if (obs) {
@@ -143,7 +141,7 @@ __device__ __forceinline__ void emit_outputs(const Lane& L, uint32_t bk, uint32_
       if (t2) atomicOr(&lds_obs[q + 2], t2);
     }
     wave_lds_fence();
-    emit_bytes<OBS_ROUNDS>(lds_obs, lut, obs + (int64_t)b0 * OBS, (uint32_t)(nb * OBS), L.lane);
+    emit_bytes<W * OBS>(lds_obs, lut, obs + (int64_t)b0 * OBS, (uint32_t)(nb * OBS), L.lane);
     wave_lds_fence();
   }
 }
@@ -379,8 +377,6 @@ __device__ __forceinline__ void stream_put(uint32_t* stream, const uint32_t (&S)
 
 constexpr int LANE_MASK_DW = ((15 + 64 * A + 31) / 32 + 3) / 4 * 4;   // LDS dwords of a wavefront's streams: 64 boards
 constexpr int LANE_OBS_DW = ((15 + 64 * OBS + 31) / 32 + 3) / 4 * 4;
-constexpr int LANE_MASK_ROUNDS = (64 * A / 16 + 63) / 64;
-constexpr int LANE_OBS_ROUNDS = (64 * OBS / 16 + 63) / 64;
 
 // rows (black bits 0-10, white bits 16-26 of one dword per row) <-> the two sets of a board
 __device__ __forceinline__ void rows_to_sets(const uint32_t (&row)[N], B128& bk, B128& wt) {
@@ -507,8 +503,8 @@ __device__ __forceinline__ void lane_emit(const B128& bk, const B128& wt, const 
     stream_put<16, 1, 14>(lds_obs, O, head + (uint32_t)(OBS * lane));
   }
   wave_lds_fence();
-  if (mask) emit_bytes<LANE_MASK_ROUNDS>(lds_mask, lut, mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
-  if (obs) emit_bytes<LANE_OBS_ROUNDS>(lds_obs, lut, obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
+  if (mask) emit_bytes<64 * A>(lds_mask, lut, mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
+  if (obs) emit_bytes<64 * OBS>(lds_obs, lut, obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
   wave_lds_fence();
 }
 

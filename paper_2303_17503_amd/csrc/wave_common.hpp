@@ -53,7 +53,9 @@ __device__ __forceinline__ void wave_lds_fence() {
 // ------------------------------------------------------------------------------------------------
 // bit stream -> byte stream.  `bits` (LDS) holds bit (head+i) = byte i of the destination, head = the
 // destination's offset from the previous 16-byte boundary.  Whole aligned 16-byte groups are written as
-// vectors (ROUNDS rounds of 64 lanes cover them all), the ragged ends byte by byte.
+// vectors, the ragged ends byte by byte.  Lane l always writes a group whose address is l*16 modulo 128, so
+// that every store instruction of the wavefront covers eight whole 128-byte lines: a 1 KB store that straddles
+// line boundaries costs a quarter more time once the lines have to reach DRAM (measured with a plain fill).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t spread4(uint32_t nibble) { return (nibble * 0x00204081u) & 0x01010101u; }
 
@@ -76,42 +78,49 @@ __device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
   }
 }
 
-template <int ROUNDS, bool NT = false>
+// MAXBYTES: upper bound of nbytes (fixes the number of rounds of 64 groups).  dst and nbytes must be the same in
+// every lane.
+template <int MAXBYTES, bool NT = false>
 __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
+  constexpr int ROUNDS = (((MAXBYTES + 15) >> 4) + 7 + 63) / 64;   // groups + the at most 7 skipped at the front
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
   uint8_t* base = dst - head;
+  const uint32_t q = ((uint32_t)(uintptr_t)base >> 4) & 7u;         // position of group 0 in its 128-byte line
   const uint32_t total = head + nbytes;
-  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;   // whole groups m0 .. m1-1, at most 64*ROUNDS of them
-  const uint32_t mine = m0 + (uint32_t)lane;             // this lane's group in round 0; round i adds 64*i
+  const uint32_t m0 = head ? 1u : 0u, m1 = total >> 4;              // whole groups m0 .. m1-1
+  const int32_t mine = lane - (int32_t)q;                           // this lane's group in round 0; round i adds 64*i
   const uint16_t* src = (const uint16_t*)bits + mine;
   uint4* out = (uint4*)base + mine;
   constexpr int GROUP = 6;   // rounds in flight at a time (bounds the registers held by pending LDS reads)
-  // Rounds in which every lane has a group need no per-lane test; with a full wavefront of boards that is all but
-  // the last round, and the choice is the same for the whole wavefront.
-  const bool full_but_last = m1 >= m0 + 64u * (uint32_t)(ROUNDS - 1);
-  if (ROUNDS > 1 && full_but_last) {
+  // Round 0 skips the groups before m0; rounds 1 .. ROUNDS-3 are full for a full wavefront of boards and then run
+  // without per-lane tests (the choice is the same for the whole wavefront).
+  const bool full_mid = m1 + q >= 64u * (uint32_t)(ROUNDS > 2 ? ROUNDS - 2 : 0);
+  auto active = [&](int i) { return mine + 64 * i >= (int32_t)m0 && mine + 64 * i < (int32_t)m1; };
+  if (full_mid) {
 #pragma unroll
-    for (int g = 0; g < ROUNDS - 1; g += GROUP) {
+    for (int g = 0; g < ROUNDS; g += GROUP) {
       uint32_t v[GROUP];
 #pragma unroll
-      for (int i = g; i < g + GROUP && i < ROUNDS - 1; ++i) v[i - g] = (uint32_t)src[64 * i];
+      for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
+        const bool test = (i == 0 || i >= ROUNDS - 2);
+        v[i - g] = (!test || active(i)) ? (uint32_t)src[64 * i] : 0u;
+      }
 #pragma unroll
-      for (int i = g; i < g + GROUP && i < ROUNDS - 1; ++i) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+      for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
+        const bool test = (i == 0 || i >= ROUNDS - 2);
+        if (!test || active(i)) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+      }
       __builtin_amdgcn_sched_barrier(0);
-    }
-    if (mine + 64u * (ROUNDS - 1) < m1) {
-      const uint32_t v = (uint32_t)src[64 * (ROUNDS - 1)];
-      store16<NT>(&out[64 * (ROUNDS - 1)], lut[v & 255u], lut[v >> 8]);
     }
   } else {
 #pragma unroll
     for (int g = 0; g < ROUNDS; g += GROUP) {
       uint32_t v[GROUP];
 #pragma unroll
-      for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = (mine + 64u * i < m1) ? (uint32_t)src[64 * i] : 0u;
+      for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = active(i) ? (uint32_t)src[64 * i] : 0u;
 #pragma unroll
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i)
-        if (mine + 64u * i < m1) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        if (active(i)) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }

@@ -90,6 +90,49 @@ def test_padded_and_misaligned_pitches(obs_pitch, mask_pitch):
     assert (p.obs[:, 6137:] == 7).all() and (p.mask[:, 362:] == 7).all()
 
 
+@pytest.mark.parametrize("N,B", [(19, 20), (19, 7), (9, 50), (9, 4)])
+def test_line_padded_pitches(N, B):
+    """Pitches rounded up to 128-byte lines: the pad bytes belong to the record and are written as zeros; step, the
+    getters, the rollout kernel and the slot call in that layout, with ragged last wavefronts."""
+    from gpu_common import Pair
+    import paper_2303_17503_amd as pg
+    P = N * N
+    op, mp = (P * 17 + 127) // 128 * 128, (P + 1 + 127) // 128 * 128
+    p = Pair(B, N, seed=8, auto_reset=True, obs_pitch=op, mask_pitch=mp)
+    assert p.env.obs_pitch == op and p.env.mask_pitch == mp
+    p.obs.fill_(7); p.mask.fill_(7)
+    p.rollout(8, 0, 150, every=1, state_every=50)
+    assert (p.obs[:, P * 17:] == 0).all() and (p.mask[:, P + 1:] == 0).all()
+    assert (p.env.obs_view(p.obs).cpu().numpy() == p.orc.observe()).all()
+    got_o, got_m = p.env.observe(), p.env.legal_mask()
+    assert torch.equal(got_o, p.obs) and torch.equal(got_m, p.mask)
+    # the same games through GoEnv(line_padded=True) and the rollout kernel, every ply in its own slice
+    T = 40
+    e = pg.GoEnv(B, N, seed=8, auto_reset=True, line_padded=True)
+    assert (e.obs_pitch, e.mask_pitch) == (op, mp)
+    obs = torch.full((T, B, op), 7, dtype=torch.uint8, device="cuda")
+    mask = torch.full((T, B, mp), 7, dtype=torch.uint8, device="cuda")
+    acts = torch.empty((T, B), dtype=torch.int32, device="cuda")
+    e.rollout(T, 8, 0, slices=T, actions=acts, mask=mask, obs=obs)
+    q = Pair(B, N, seed=8, auto_reset=True, bind=False)
+    for t in range(T):
+        a = q.orc.random_actions(8, t)
+        assert (acts[t].cpu().numpy() == a).all()
+        q.orc.step(a)
+        assert (mask[t, :, :P + 1].cpu().numpy() == q.orc.legal_mask()).all(), t
+        assert (obs[t, :, :P * 17].cpu().numpy().reshape(B, N, N, 17) == q.orc.observe()).all(), t
+    assert (obs[:, :, P * 17:] == 0).all() and (mask[:, :, P + 1:] == 0).all()
+    # slot call: every game stepped into itself with a random legal action
+    idx = torch.arange(B, dtype=torch.int32, device="cuda")
+    a = q.orc.random_actions(8, T)
+    m2, o2 = e.new_mask().fill_(7), e.new_obs().fill_(7)
+    e.step_slots(idx, torch.as_tensor(a, device="cuda"), idx, mask=m2, obs=o2)
+    q.orc.step(a)
+    assert (m2[:, :P + 1].cpu().numpy() == q.orc.legal_mask()).all()
+    assert (e.obs_view(o2).cpu().numpy() == q.orc.observe()).all()
+    assert (o2[:, P * 17:] == 0).all() and (m2[:, P + 1:] == 0).all()
+
+
 def test_misaligned_output_base_pointers():
     from gpu_common import Pair
     import paper_2303_17503_amd as pg
