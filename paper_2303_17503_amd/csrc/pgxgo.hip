@@ -211,27 +211,41 @@ __device__ __forceinline__ void store_row(uint4* __restrict__ planes, size_t row
   }
 }
 
-// Stores only the planes of this row whose content differs from `Old` (what the kernel loaded).  With colours
-// stored absolutely, a history word changes only while its point changed within the last 8 plies, so most
-// rows of most planes are unchanged from ply to ply.
+// The four row words as loaded, kept to tell at store time which of them changed.
+struct RowWords {
+  uint32_t bk, wt, ab, aw;
+};
 template <int N>
-__device__ __forceinline__ void store_row_changed(uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, const Row<N>& R, const Row<N>& Old) {
+__device__ __forceinline__ RowWords row_words(const Row<N>& R) { return RowWords{R.bk, R.wt, R.ab, R.aw}; }
+
+// Stores only the 16-byte planes of this row whose content differs from what the kernel loaded.  With colours
+// stored absolutely, a history word changes only while its point changed within the last 8 plies, so most
+// rows of most planes are unchanged from ply to ply.  hdirty: bit k set = a history dword of plane k changed (from
+// push_history; all ones after a reset); Old: the row words as loaded.
+template <int N>
+__device__ __forceinline__ void store_row_changed(uint4* __restrict__ planes, size_t rows_total, const Lane<N>& L, const Row<N>& R, uint32_t hdirty,
+                                                  const RowWords& Old) {
   using G = Geo<N>;
-  uint32_t rec[G::NQ * 4 + 4], old[G::NQ * 4 + 4];
+  uint32_t rec[G::NQ * 4 + 4], dif[G::NQ * 4 + 4];
 #pragma unroll
-  for (int k = 0; k < G::HD; ++k) { rec[k] = R.h[k]; old[k] = Old.h[k]; }
+  for (int k = 0; k < G::NQ * 4 + 4; ++k) { rec[k] = 0u; dif[k] = 0u; }
+#pragma unroll
+  for (int k = 0; k < G::HD; ++k) rec[k] = R.h[k];
   rec[G::HD] = R.bk; rec[G::HD + 1] = R.wt; rec[G::HD + 2] = R.ab; rec[G::HD + 3] = R.aw;
-  old[G::HD] = Old.bk; old[G::HD + 1] = Old.wt; old[G::HD + 2] = Old.ab; old[G::HD + 3] = Old.aw;
+  dif[G::HD] = R.bk ^ Old.bk; dif[G::HD + 1] = R.wt ^ Old.wt; dif[G::HD + 2] = R.ab ^ Old.ab; dif[G::HD + 3] = R.aw ^ Old.aw;
   if (L.valid) {
     const size_t idx = (size_t)L.slot * N + L.r;
 #pragma unroll
-    for (int k = 0; k < G::NQ; ++k) {
-      const uint32_t diff = (rec[4 * k] ^ old[4 * k]) | (rec[4 * k + 1] ^ old[4 * k + 1]) | (rec[4 * k + 2] ^ old[4 * k + 2]) | (rec[4 * k + 3] ^ old[4 * k + 3]);
-      if (diff) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
+    for (int k = 0; k <= G::NQ; ++k) {   // k = NQ: the narrower last plane
+      const uint32_t diff = ((hdirty >> k) & 1u) | dif[4 * k] | dif[4 * k + 1] | dif[4 * k + 2] | dif[4 * k + 3];
+      if (k < G::NQ) {
+        if (diff) planes[(size_t)k * rows_total + idx] = make_uint4(rec[4 * k], rec[4 * k + 1], rec[4 * k + 2], rec[4 * k + 3]);
+      } else {
+        uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
+        if constexpr (G::REM == 2) { if (diff) *(uint2*)(tail + idx * 2) = make_uint2(rec[4 * G::NQ], rec[4 * G::NQ + 1]); }
+        if constexpr (G::REM == 1) { if (diff) tail[idx] = rec[4 * G::NQ]; }
+      }
     }
-    uint32_t* tail = (uint32_t*)(planes + (size_t)G::NQ * rows_total);
-    if constexpr (G::REM == 2) { if ((rec[4 * G::NQ] ^ old[4 * G::NQ]) | (rec[4 * G::NQ + 1] ^ old[4 * G::NQ + 1])) *(uint2*)(tail + idx * 2) = make_uint2(rec[4 * G::NQ], rec[4 * G::NQ + 1]); }
-    if constexpr (G::REM == 1) { if (rec[4 * G::NQ] != old[4 * G::NQ]) tail[idx] = rec[4 * G::NQ]; }
   }
 }
 
@@ -251,7 +265,7 @@ __device__ __forceinline__ uint32_t legal_row(const Lane<N>& L, const Row<N>& R,
 // Legal mask bytes [N*N+1] of every board of the wavefront.  TIGHT: the pitch is the dense one (N*N+1) or the
 // line-padded one (A_PAD); the boards of a wavefront are then one contiguous run of bytes, pad bytes included, and
 // are staged and written as one stream (the pad bytes as zeros); otherwise board by board, pad bytes untouched.
-template <int N, bool TIGHT, bool NT = false>
+template <int N, bool TIGHT, int ST = kStorePlain>
 __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int wave, int B, uint8_t* mask, int64_t mask_pitch,
                                           uint32_t* lds_mask, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
@@ -274,17 +288,17 @@ __device__ __forceinline__ void emit_mask(const Lane<N>& L, uint32_t legal, int 
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<G::W * G::A_PAD, NT>(lds_mask, lut, mask + (int64_t)b0 * mask_pitch, (uint32_t)nb * stride, L.lane);
+    emit_bytes<G::W * G::A_PAD, ST>(lds_mask, lut, mask + (int64_t)b0 * mask_pitch, (uint32_t)nb * stride, L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::A, NT>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
+      if (jj < nb) emit_bytes<G::A, ST>(lds_mask + jj * G::MASK_DW, lut, mask + (int64_t)(b0 + jj) * mask_pitch, G::A, L.lane);
   }
   wave_lds_fence();
 }
 
 // Observation bytes [N][N][17] of every board of the wavefront from the history words h of its rows.
-template <int N, bool TIGHT, bool NT = false>
+template <int N, bool TIGHT, int ST = kStorePlain>
 __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[Geo<N>::HD], int wtm, int wave, int B, uint8_t* obs,
                                          int64_t obs_pitch, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
   using G = Geo<N>;
@@ -346,21 +360,21 @@ __device__ __forceinline__ void emit_obs(const Lane<N>& L, const uint32_t (&h)[G
   }
   wave_lds_fence();
   if constexpr (tight) {
-    emit_bytes<G::W * G::OBS_PAD, NT>(lds_obs, lut, obs + (int64_t)b0 * obs_pitch, (uint32_t)nb * stride, L.lane);
+    emit_bytes<G::W * G::OBS_PAD, ST>(lds_obs, lut, obs + (int64_t)b0 * obs_pitch, (uint32_t)nb * stride, L.lane);
   } else {
 #pragma unroll
     for (int jj = 0; jj < G::W; ++jj)
-      if (jj < nb) emit_bytes<G::OBS, NT>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
+      if (jj < nb) emit_bytes<G::OBS, ST>(lds_obs + jj * G::OBS_DW, lut, obs + (int64_t)(b0 + jj) * obs_pitch, G::OBS, L.lane);
   }
   wave_lds_fence();
 }
 
-template <int N, bool TIGHT, bool NT = false>
+template <int N, bool TIGHT, int ST = kStorePlain>
 __device__ __forceinline__ void emit_outputs(const Lane<N>& L, const Row<N>& R, uint32_t legal, int wtm, int wave, int B,
                                              uint8_t* mask, int64_t mask_pitch, uint8_t* obs, int64_t obs_pitch,
                                              uint32_t* lds_mask, uint32_t* lds_obs, const uint2* lut, int wb = Geo<N>::W) {
-  if (mask) emit_mask<N, TIGHT, NT>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
-  if (obs) emit_obs<N, TIGHT, NT>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
+  if (mask) emit_mask<N, TIGHT, ST>(L, legal, wave, B, mask, mask_pitch, lds_mask, lut, wb);
+  if (obs) emit_obs<N, TIGHT, ST>(L, R.h, wtm, wave, B, obs, obs_pitch, lds_obs, lut, wb);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -446,16 +460,24 @@ __device__ __forceinline__ Move gate_move(const Lane<N>& L, const Row<N>& R, con
 }
 
 // history push: every halfword shifts by one ply and takes the position (bk, wt) in its low bits
+// hdirty: bit k is set when a history dword of the row record's 16-byte plane k changed
 template <int N>
-__device__ __forceinline__ void push_history(uint32_t (&h)[Geo<N>::HD], uint32_t bk, uint32_t wt, bool moved) {
+__device__ __forceinline__ void push_history(uint32_t (&h)[Geo<N>::HD], uint32_t bk, uint32_t wt, bool moved, uint32_t& hdirty) {
   const uint32_t lo = (bk & 0x55555555u) | ((wt & 0x55555555u) << 1);   // bit 2j / 2j+1: black / white at column 2j
   const uint32_t hi = ((bk >> 1) & 0x55555555u) | (wt & 0xAAAAAAAAu);   // the same for column 2j+1
+  uint32_t acc[(Geo<N>::HD + 3) / 4];
+#pragma unroll
+  for (int k = 0; k < (Geo<N>::HD + 3) / 4; ++k) acc[k] = 0u;
 #pragma unroll
   for (int jd = 0; jd < Geo<N>::HD; ++jd) {
     const uint32_t cur = ((lo >> (2 * jd)) & 3u) | (((hi >> (2 * jd)) & 3u) << 16);
     const uint32_t pushed = ((h[jd] << 2) & 0xFFFCFFFCu) | cur;
+    acc[jd / 4] |= moved ? (pushed ^ h[jd]) : 0u;
     h[jd] = moved ? pushed : h[jd];
   }
+  hdirty = 0u;
+#pragma unroll
+  for (int k = 0; k < (Geo<N>::HD + 3) / 4; ++k) hdirty |= acc[k] ? (1u << k) : 0u;
 }
 
 // a8: back to the initial state of the next episode (Sec. 4.1); the seat is drawn anew
@@ -472,9 +494,10 @@ __device__ __forceinline__ void reset_board(const Lane<N>& L, Row<N>& R, Meta& m
 // a3-a8 for every board of the wavefront; registers in, registers out.
 // Out: rewards by player id, `flag` = the terminated output (game ended in this ply, or had ended before),
 // `captured` = the stones this ply removed, `reset` = the board was re-initialised by auto-reset.
+// `hdirty` = which planes of the row record hold a changed history dword (see push_history; all ones after a reset).
 template <int N>
 __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, const Move& mv, float& rew0, float& rew1,
-                                           bool& flag, uint32_t& captured, bool& reset) {
+                                           bool& flag, uint32_t& captured, bool& reset, uint32_t& hdirty) {
   using G = Geo<N>;
   const bool playing = mv.playing, is_pass = mv.is_pass, illegal = mv.illegal, frozen = mv.frozen;
   const int pr = mv.pr, pc = mv.pc;
@@ -572,7 +595,7 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
     m.wtm ^= 1;
   }
   // ---- a6: history push ---------------------------------------------------------------------------------
-  push_history<N>(R.h, R.bk, R.wt, moved);
+  push_history<N>(R.h, R.bk, R.wt, moved, hdirty);
 
   // ---- a7: termination and Tromp-Taylor area score ------------------------------------------------------
   const bool score = moved && (m.passes >= 2 || m.steps >= cfg.max_steps);
@@ -606,9 +629,15 @@ __device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m,
   if (ended) {
     m.term = 1;
     // ---- a8: auto-reset (Sec. 4.1) -------------------------------------------------------------------------
-    if (cfg.auto_reset) reset_board<N>(L, R, m, cfg.seed);
+    if (cfg.auto_reset) { reset_board<N>(L, R, m, cfg.seed); hdirty = ~0u; }
   }
   flag = ended || frozen;
+}
+template <int N>
+__device__ __forceinline__ void apply_move(const Lane<N>& L, Row<N>& R, Meta& m, const Rules& cfg, const Move& mv, float& rew0, float& rew1,
+                                           bool& flag, uint32_t& captured, bool& reset) {
+  uint32_t hdirty;
+  apply_move<N>(L, R, m, cfg, mv, rew0, rew1, flag, captured, reset, hdirty);
 }
 
 template <int N, bool GATE>
@@ -634,7 +663,7 @@ struct StepArgs {
   int64_t mask_pitch, obs_pitch;
   int B;
   int wb;                    // boards per wavefront of this launch
-  int nt_store;              // non-temporal output stores (launches that write far more than the memory-side cache holds)
+  int store_kind;            // kind of the output stores (kStorePlain / kStoreStream / kStoreThrough), by the bytes a launch writes
   int sparse_store;
   Rules rules;
   // fused sampler
@@ -643,7 +672,7 @@ struct StepArgs {
   int32_t* next_actions;
 };
 
-template <int N, bool SAMPLE, bool TIGHT, bool NT>
+template <int N, bool SAMPLE, bool TIGHT, int ST>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -659,9 +688,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   load_row<N>(a.planes, rows_total, L, R);
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
+  // loaded here and not where it is used: a load after the output stores would have to wait for them (one counter)
+  const bool wait_start = SAMPLE && L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
   fill_spread_table(lut);
   if (wave * a.wb >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
-  const Row<N> R_loaded = R;
+  const RowWords W_loaded = row_words<N>(R);
   Meta m = unpack_meta(meta_raw);
 
   // a1/a2: decode the action and gate it
@@ -673,29 +704,28 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   // a3-a8
   float rew0, rew1;
   bool flag, reset;
-  uint32_t captured;
-  apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset);
+  uint32_t captured, hdirty;
+  apply_move<N>(L, R, m, a.rules, mv, rew0, rew1, flag, captured, reset, hdirty);
   if (!skip && L.valid && L.r == 0) {
     *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
 
   // ---- a10 / a9: observation and legal mask of the player now to move ---------------------------------------
-  if (a.obs) emit_obs<N, TIGHT, NT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+  if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko);
-  if (a.mask) emit_mask<N, TIGHT, NT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
+  if (a.mask) emit_mask<N, TIGHT, ST>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
 
   // ---- a11: store the state --------------------------------------------------------------------------------
   if (!skip) {
     // Writing only the changed planes pays while state and outputs stay resident in the memory-side cache
     // (partial lines merge there); beyond it partial lines cost a read-modify-write in DRAM and whole rows win.
-    if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, R_loaded);
+    if (a.sparse_store) store_row_changed<N>(a.planes, rows_total, L, R, hdirty, W_loaded);
     else store_row<N>(a.planes, rows_total, L, R);
     if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
   }
   if (SAMPLE) {
-    const bool wait = L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
-    const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
+    const Draw<N> d = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait_start);
     if (L.valid && L.r == 0) a.next_actions[L.b] = d.action();
   }
 }
@@ -854,12 +884,15 @@ __device__ __forceinline__ void sk_walk(const Lane<N>& L, const uint2* tab, uint
     if (__ballot(!done) == 0ull) break;
     const bool look = L.valid && (uint32_t)L.r < WIN && !done;
     uint2 e = make_uint2(1u, 0u);
-    if (look) {
-      const uint32_t slot = (base + (uint32_t)L.r) & Zt<N>::MASK;
-      if (round == 0u && pre.home == base) e = pre.e;
-      else e = tab_load(&tab[slot]);
-      if (slot == taken && (e.x | e.y) == 0u) e = make_uint2(1u, 0u);
+    const uint32_t slot = (base + (uint32_t)L.r) & Zt<N>::MASK;
+    const bool from_pre = round == 0u && pre.home == base;
+    if (look && from_pre) e = pre.e;
+    if (__ballot(look && !from_pre) != 0ull) {   // a branch of the whole wavefront: most walks end in the window loaded ahead
+      if (look && !from_pre) e = tab_load(&tab[slot]);
+      // the wait for this load stays inside the branch: after it, it would also be a wait for the caller's output stores
+      asm volatile("" : "+v"(e.x), "+v"(e.y));
     }
+    if (look && slot == taken && (e.x | e.y) == 0u) e = make_uint2(1u, 0u);
     visit(e, look);
     const uint64_t em = __ballot(look && (e.x | e.y) == 0u) & seg;
     if (!done) {
@@ -1030,10 +1063,15 @@ __device__ __forceinline__ void sk_clear_tables(const Lane<N>& L, bool flagged, 
 // legality gate only if it is not one of the position's forbidden plays (`forb`, updated to those of the new position),
 // the new position goes into the table, an auto-reset clears it.  tab_r / tab_w / game: see sk_insert, sk_clear_tables.
 // GATE as in gate_move.  Out: as apply_move.
-template <int N, bool GATE>
+// board_final(hdirty) is called once the rows and scalars of the new position (an auto-reset included) are final: the
+// caller emits the observation and may store the state there.  EARLY: before the table work, so that those stores are
+// under way while the walks go on (measured: 25.1 -> 23.8 us per ply in the rollout kernel; in the one-launch-per-ply
+// kernel it is 1 us slower than calling it afterwards, hence the choice).
+template <int N, bool GATE, bool EARLY, class Hook>
 __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& m, SkGame& g, uint32_t& forb, const Rules& rules, bool skip, bool want_pass,
                                              bool want_point, int pr_in, int pc_in, const uint2* tab_r, uint2* tab_w, uint2* zt, int game,
-                                             uint32_t* scratch, float& rew0, float& rew1, bool& flag, bool pre_a_loaded, const SkWin& pre_a) {
+                                             uint32_t* scratch, float& rew0, float& rew1, bool& flag, bool pre_a_loaded, const SkWin& pre_a,
+                                             Hook&& board_final) {   // board_final(hdirty): hdirty as from apply_move
   const int c = m.wtm, own = c ? g.nw : g.nb, opp = c ? g.nb : g.nw;
   Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
   // a play the simple rules allow but the repetition rule forbids is an illegal action
@@ -1053,16 +1091,25 @@ __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& 
   r0.auto_reset = 0;   // the reset happens below, after the table work
   bool reset;
   uint32_t captured;
-  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset);
-  const SkPly s = sk_look<N>(L, tab_r, g, c, mv, captured, pre[0], scratch);
+  uint32_t hdirty;
+  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
   const bool do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
+  if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }   // a board that is reset takes no part in the table work below
+  if constexpr (EARLY) {
+    // The windows have to be in registers before the caller's stores are issued: loads and stores share one counter,
+    // and a wait for these loads placed after the stores would wait for the stores as well.
+    asm volatile("" ::"v"(pre[0].e.x), "v"(pre[0].e.y), "v"(pre[1].e.x), "v"(pre[1].e.y), "v"(pre[2].e.x), "v"(pre[2].e.y));
+    board_final(hdirty);
+  }
+  const SkPly s = sk_look<N>(L, tab_r, g, c, mv, captured, pre[0], scratch);
   sk_insert<N>(L, tab_r, tab_w, g, s, mv.playing && !do_reset, c, pre[2]);
   // the forbidden plays change with the position and with the player to move; otherwise they stay
   const bool moved = (mv.playing || mv.is_pass) && !do_reset;
   const uint32_t fresh = sk_forbidden<N>(L, tab_r, g, R, m, moved, pre[1], scratch);
   if (moved) forb = fresh;
-  if (do_reset) { reset_board<N>(L, R, m, rules.seed); g = sk_fresh(); forb = 0u; }
+  if (do_reset) { g = sk_fresh(); forb = 0u; }
   sk_clear_tables<N>(L, do_reset, zt, game);
+  if constexpr (!EARLY) board_final(hdirty);
 }
 
 // One ply with the repetition rule.  Same steps as go_step_kernel.
@@ -1081,6 +1128,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
   SkGame g = L.boardok ? sk_unpack(zcur[L.b]) : sk_fresh();
+  const bool wait_start = a.next_actions && L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
   fill_spread_table(lut);
   if (wave * a.wb >= a.B) return;
   Meta m = unpack_meta(meta_raw);
@@ -1094,23 +1142,25 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   uint32_t forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
   float rew0, rew1;
   bool flag;
-  sk_step_core<N, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none);
+  sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
+                               false, none, [&](uint32_t) {   // a10, a11 (whole rows: writing only the changed planes gains nothing here)
+                                 if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+                                 if (!skip) {
+                                   store_row<N>(a.planes, rows_total, L, R);
+                                   if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+                                 }
+                               });
   if (!skip && L.valid && L.r == 0) {
     *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
   g.fw = sk_forb_word<N>(L, forb);
 
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(mode == 2 ? forb : 0u);
   if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
-  if (!skip) {
-    store_row<N>(a.planes, rows_total, L, R);
-    if (L.valid && L.r == 0) { a.meta[L.b] = pack_meta(m); zcur[L.b] = sk_pack(g); }
-  }
+  if (!skip && L.valid && L.r == 0) zcur[L.b] = sk_pack(g);
   if (a.next_actions) {
-    const bool wait = L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
-    const Draw<N> dr = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait);
+    const Draw<N> dr = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait_start);
     if (L.valid && L.r == 0) a.next_actions[L.b] = dr.action();
   }
 }
@@ -1188,7 +1238,7 @@ struct SlotArgs {
 };
 
 // SK: the positional-superko rule is on; a game that moves to another slot takes its key table along.
-template <int N, bool TIGHT, bool SK>
+template <int N, bool TIGHT, bool SK, int ST = kStorePlain>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots_kernel(SlotArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -1238,8 +1288,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
     SkWin none;
     none.home = ~0u; none.e = make_uint2(1u, 0u);
     forb = sk_forb_loaded<N>(L, tab_r, g, R, m, none, lds_mask_all[wib]);
-    sk_step_core<N, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, false,
-                          none);
+    sk_step_core<N, true, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, false,
+                          none, [&](uint32_t) { if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut); });
     g.fw = sk_forb_word<N>(L, forb);
     if (L.valid && L.r == 0) a.zcur[dslot] = sk_pack(g);
     if (a.sk_mode != 2) forb = 0u;   // the mask shows the simple-ko set unless the rule proper is on
@@ -1253,8 +1303,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
     }
   }
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~forb;
-  if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
+  if constexpr (!SK) { if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut); }
+  if (a.mask) emit_mask<N, TIGHT, ST>(L, legal, wave, a.n, a.mask, a.mask_pitch, lds_mask_all[wib], lut);
   store_row<N>(a.planes, rows_total, L, R);
   if (L.valid && L.r == 0) a.meta[dst] = pack_meta(m);
 }
@@ -1269,7 +1319,6 @@ struct RolloutArgs {
   uint4* meta;
   int B;
   int wb;               // boards per wavefront of this launch
-  int nt_store;         // non-temporal output stores
   Rules rules;
   int steps, slices;
   uint32_t seed, t0;
@@ -1328,7 +1377,9 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
     } else {
       SkWin none;
       none.home = ~0u; none.e = make_uint2(1u, 0u);
-      sk_step_core<N, false>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none);
+      uint8_t* const obs_t = a.obs ? a.obs + (size_t)slice * a.B * a.obs_pitch : nullptr;
+      sk_step_core<N, false, true>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none,
+                             [&](uint32_t) { if (obs_t) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb); });
       legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(a.sk_mode == 2 ? forb : 0u);
     }
     const size_t sb = (size_t)slice * a.B;
@@ -1340,7 +1391,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
     emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
-                    a.obs ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
+                    (!SK && a.obs) ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
   }
@@ -1622,6 +1673,11 @@ unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + 
 // observation, the hint costs 20-30 % up to ~50 k games (everything still fits the 256 MB memory-side cache together
 // with the state) and gains 9-17 % from ~57 k games on.
 constexpr size_t kNonTemporalFrom = (size_t)350 << 20;
+// ... and up to which they are written through the L2 (measured at 19x19 with the observation: 6-12 % faster for 1024
+// to 6144 games, even at 8192 games = 53 MB, slower beyond).  The rollout kernel uses plain stores at every size (both
+// other kinds were measured slower there).
+constexpr size_t kWriteThroughUpTo = (size_t)48 << 20;
+int store_kind_for(size_t out_bytes) { return out_bytes > kNonTemporalFrom ? kStoreStream : (out_bytes <= kWriteThroughUpTo ? kStoreThrough : kStorePlain); }
 size_t output_bytes_per_ply(const pgxgo_ctx* h, bool with_mask, bool with_obs) {
   return (size_t)h->B * ((with_mask ? (size_t)h->mask_pitch : 0) + (with_obs ? (size_t)h->obs_pitch : 0));
 }
@@ -1667,7 +1723,7 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   // bytes one ply touches: state rows + outputs; 256 MB of memory-side cache on this part, keep a margin
   const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
-  a.nt_store = output_bytes_per_ply(h, h->mask_out != nullptr, h->obs_out != nullptr) > kNonTemporalFrom ? 1 : 0;
+  a.store_kind = store_kind_for(output_bytes_per_ply(h, h->mask_out != nullptr, h->obs_out != nullptr));
   const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
@@ -1677,11 +1733,11 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
     HIPCHK(hipGetLastError());
     return PGXGO_OK;
   }
-  const bool nt = a.nt_store != 0;
   auto go = [&](auto sample_c, auto tight_c) {
     constexpr bool S = decltype(sample_c)::value, T = decltype(tight_c)::value;
-    if (nt) hipLaunchKernelGGL((go_step_kernel<N, S, T, true>), grid, block, 0, h->stream, a);
-    else hipLaunchKernelGGL((go_step_kernel<N, S, T, false>), grid, block, 0, h->stream, a);
+    if (a.store_kind == kStoreStream) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreStream>), grid, block, 0, h->stream, a);
+    else if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThrough>), grid, block, 0, h->stream, a);
+    else hipLaunchKernelGGL((go_step_kernel<N, S, T, kStorePlain>), grid, block, 0, h->stream, a);
   };
   if (sample && tight) go(std::true_type{}, std::true_type{});
   else if (sample) go(std::true_type{}, std::false_type{});
@@ -1719,7 +1775,10 @@ template <int N>
 int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
   const dim3 grid(blocks_for<N>(a.n)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
+  const size_t out_bytes = (size_t)a.n * ((a.mask ? (size_t)a.mask_pitch : 0) + (a.obs ? (size_t)a.obs_pitch : 0));
   if (tight && sk) hipLaunchKernelGGL((go_step_slots_kernel<N, true, true>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes) == kStoreStream) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreStream>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes) == kStoreThrough) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThrough>), grid, block, 0, h->stream, a);
   else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false>), grid, block, 0, h->stream, a);
   else if (sk) hipLaunchKernelGGL((go_step_slots_kernel<N, false, true>), grid, block, 0, h->stream, a);
   else hipLaunchKernelGGL((go_step_slots_kernel<N, false, false>), grid, block, 0, h->stream, a);
@@ -1923,7 +1982,6 @@ int pgxgo_rollout(pgxgo_t h, int32_t steps, int32_t slices, uint32_t seed, uint3
   if (steps == 0) return PGXGO_OK;
   RolloutArgs a;
   a.planes = h->planes; a.meta = h->meta; a.B = h->B; a.wb = h->wb;
-  a.nt_store = 0;   // measured: the hint slows the rollout kernel down at every size (96 vs 62 us per ply at 65536 games)
   a.rules.seed = h->seed; a.rules.komi_x2 = h->komi_x2; a.rules.max_steps = h->max_steps; a.rules.auto_reset = h->auto_reset;
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;

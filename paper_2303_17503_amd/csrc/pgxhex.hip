@@ -121,7 +121,7 @@ __device__ __forceinline__ void emit_outputs(const Lane& L, uint32_t bk, uint32_
       if (L.r == 0 && swap) { const uint32_t o2 = head + P; atomicOr(&lds_mask[o2 >> 5], 1u << (o2 & 31u)); }
     }
     wave_lds_fence();
-    emit_bytes<W * A>(lds_mask, lut, mask + (int64_t)b0 * A, (uint32_t)(nb * A), L.lane);
+    emit_bytes<W * A, kStoreThrough>(lds_mask, lut, mask + (int64_t)b0 * A, (uint32_t)(nb * A), L.lane);
     wave_lds_fence();
   }
   if (obs) {
@@ -141,7 +141,7 @@ __device__ __forceinline__ void emit_outputs(const Lane& L, uint32_t bk, uint32_
       if (t2) atomicOr(&lds_obs[q + 2], t2);
     }
     wave_lds_fence();
-    emit_bytes<W * OBS>(lds_obs, lut, obs + (int64_t)b0 * OBS, (uint32_t)(nb * OBS), L.lane);
+    emit_bytes<W * OBS, kStoreThrough>(lds_obs, lut, obs + (int64_t)b0 * OBS, (uint32_t)(nb * OBS), L.lane);
     wave_lds_fence();
   }
 }
@@ -282,6 +282,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
   const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
+  // loaded with the state: a load issued after the output stores would have to wait for them (one counter)
+  const bool wait_start = SAMPLE && a.start_t && L.boardok && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
   fill_spread_table(lut);
   if (wave * W >= a.B) return;
 
@@ -299,8 +301,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   emit_outputs(L, bk, wt, m, wave, a.B, a.mask, a.obs, lds_mask[wib], lds_obs[wib], lut);
 
   if (SAMPLE) {
-    const bool wait = a.start_t && L.boardok && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
-    const int next = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.sample_seed, a.sample_t, wait);
+    const int next = draw_action(L, L.full & ~(bk | wt), m.steps == 1, a.sample_seed, a.sample_t, wait_start);
     if (L.valid && L.r == 0) a.next_actions[L.b] = next;
   }
 }
@@ -503,8 +504,8 @@ __device__ __forceinline__ void lane_emit(const B128& bk, const B128& wt, const 
     stream_put<16, 1, 14>(lds_obs, O, head + (uint32_t)(OBS * lane));
   }
   wave_lds_fence();
-  if (mask) emit_bytes<64 * A>(lds_mask, lut, mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
-  if (obs) emit_bytes<64 * OBS>(lds_obs, lut, obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
+  if (mask) emit_bytes<64 * A, kStoreThrough>(lds_mask, lut, mask + (size_t)b0 * A, (uint32_t)(nb * A), lane);
+  if (obs) emit_bytes<64 * OBS, kStoreThrough>(lds_obs, lut, obs + (size_t)b0 * OBS, (uint32_t)(nb * OBS), lane);
   wave_lds_fence();
 }
 
@@ -543,6 +544,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
   for (int r = 0; r < N; ++r) row[r] = ok ? a.rows[(size_t)b * N + r] : 0u;
   const uint4 mv = ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u);
   const int act = ok ? a.actions[b] : -1;
+  // loaded with the state: a load issued after the output stores would have to wait for them (one counter)
+  const bool wait_start = SAMPLE && a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
   fill_spread4_table(lut4);
   fill_spread_table(lut);                   // ends with the block's only barrier
   if (b0 >= a.B) return;
@@ -567,8 +570,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
   const B128 legal = lane_legal(bk, wt, m);
   lane_emit(bk, wt, m, legal, ok, lane, b0, nb, a.mask, a.obs, lds_mask[wib], lds_obs[wib], lut, lut4);
   if (SAMPLE) {
-    const bool wait = a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
-    const int next = lane_draw(legal, a.sample_seed, (uint32_t)b, a.sample_t, wait);
+    const int next = lane_draw(legal, a.sample_seed, (uint32_t)b, a.sample_t, wait_start);
     if (ok) a.next_actions[b] = next;
   }
 }

@@ -65,22 +65,31 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
   __syncthreads();
 }
 
-// NT: store the vectors with the non-temporal hint.  That pays only when a launch writes far more than the
-// memory-side cache holds; below that size it is slower.  dst and nbytes must be the same in every lane.
-template <bool NT>
+// The 16-byte output stores, three kinds:
+//   kStorePlain   ordinary store (write-back in the compute die's L2);
+//   kStoreStream  with the non-temporal hint, for launches that write far more than the memory-side cache holds
+//                 (below that size it is slower);
+//   kStoreThrough written through the L2 to the memory-side level (`sc1`).  Lines left dirty in the L2 have to be
+//                 written back when the kernel ends: a plain fill of 106 MB pays 1.3 of its 16.8 us for that.  It pays
+//                 for launches that write up to ~48 MB and for streams made of whole 128-byte lines whose buffers
+//                 stay in the memory-side cache; for larger ragged streams and for buffers that have to reach DRAM
+//                 it is slower than the plain store (all measured).
+// The compiler has no builtin for a 16-byte store with the `sc1` modifier, hence the instruction itself; the wait
+// state after it is the one the hardware asks for between a store of more than 8 bytes and a write to its data
+// registers.
+constexpr int kStorePlain = 0, kStoreStream = 1, kStoreThrough = 2;
+template <int KIND>
 __device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
-  if constexpr (NT) {
-    typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
-    const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
-    __builtin_nontemporal_store(v4, (vec4u*)p);
-  } else {
-    *p = make_uint4(lo.x, lo.y, hi.x, hi.y);
-  }
+  typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
+  const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
+  if constexpr (KIND == kStorePlain) *p = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  else if constexpr (KIND == kStoreStream) __builtin_nontemporal_store(v4, (vec4u*)p);
+  else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(v4) : "memory");
 }
 
 // MAXBYTES: upper bound of nbytes (fixes the number of rounds of 64 groups).  dst and nbytes must be the same in
 // every lane.
-template <int MAXBYTES, bool NT = false>
+template <int MAXBYTES, int ST = kStorePlain>
 __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lut, uint8_t* dst, uint32_t nbytes, int lane) {
   constexpr int ROUNDS = (((MAXBYTES + 15) >> 4) + 7 + 63) / 64;   // groups + the at most 7 skipped at the front
   const uint32_t head = (uint32_t)((uintptr_t)dst & 15u);
@@ -108,7 +117,7 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
 #pragma unroll
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
         const bool test = (i == 0 || i >= ROUNDS - 2);
-        if (!test || active(i)) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        if (!test || active(i)) store16<ST>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -120,7 +129,7 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = active(i) ? (uint32_t)src[64 * i] : 0u;
 #pragma unroll
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i)
-        if (active(i)) store16<NT>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        if (active(i)) store16<ST>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
