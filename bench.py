@@ -367,18 +367,20 @@ def bench_go(args, cfg):
         torch.cuda.synchronize()
         first = st.t
         # the timed region, cut into five segments by events on the same stream (median and best segment are reported too)
-        cuts = [K * i // 5 for i in range(6)]
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        # (only when there are enough launches that the four extra event records between them do not matter)
+        nseg = 5 if K >= 100 else 1
+        cuts = [K * i // nseg for i in range(nseg + 1)]
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(nseg - 1)]
         t0 = time.perf_counter()
         ev0.record()
-        for i in range(5):
+        for i in range(nseg):
             st.run(cuts[i + 1] - cuts[i])
-            if i < 4: marks[i].record()
+            if i < nseg - 1: marks[i].record()
         ev1.record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         evs = [ev0] + marks + [ev1]
-        seg_ms = [evs[i].elapsed_time(evs[i + 1]) / max(1, cuts[i + 1] - cuts[i]) for i in range(5)] if K >= 5 else []
+        seg_ms = [evs[i].elapsed_time(evs[i + 1]) / max(1, cuts[i + 1] - cuts[i]) for i in range(5)] if nseg == 5 else []
         kern_ms = ev0.elapsed_time(ev1) / K   # fused: K launches of the one kernel back to back on the stream the events are on
         if args.mode == "separate":           # the step kernel alone, an event pair around each launch
             n_ev = min(K, 500)

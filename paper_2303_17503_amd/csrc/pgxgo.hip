@@ -663,7 +663,7 @@ struct StepArgs {
   int64_t mask_pitch, obs_pitch;
   int B;
   int wb;                    // boards per wavefront of this launch
-  int store_kind;            // kind of the output stores (kStorePlain / kStoreStream / kStoreThrough), by the bytes a launch writes
+  int store_kind;            // kind of the output stores, by the bytes the launch writes (store_kind_for)
   int sparse_store;
   Rules rules;
   // fused sampler
@@ -1113,7 +1113,7 @@ __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& 
 }
 
 // One ply with the repetition rule.  Same steps as go_step_kernel.
-template <int N, bool TIGHT>
+template <int N, bool TIGHT, int ST>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur, int mode) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -1144,7 +1144,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   bool flag;
   sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
                                false, none, [&](uint32_t) {   // a10, a11 (whole rows: writing only the changed planes gains nothing here)
-                                 if (a.obs) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+                                 if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
                                  if (!skip) {
                                    store_row<N>(a.planes, rows_total, L, R);
                                    if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
@@ -1157,7 +1157,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   g.fw = sk_forb_word<N>(L, forb);
 
   const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(mode == 2 ? forb : 0u);
-  if (a.mask) emit_mask<N, TIGHT>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
+  if (a.mask) emit_mask<N, TIGHT, ST>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
   if (!skip && L.valid && L.r == 0) zcur[L.b] = sk_pack(g);
   if (a.next_actions) {
     const Draw<N> dr = draw_action<N>(L, legal, a.sample_seed, a.sample_t, wait_start);
@@ -1379,7 +1379,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       none.home = ~0u; none.e = make_uint2(1u, 0u);
       uint8_t* const obs_t = a.obs ? a.obs + (size_t)slice * a.B * a.obs_pitch : nullptr;
       sk_step_core<N, false, true>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none,
-                             [&](uint32_t) { if (obs_t) emit_obs<N, TIGHT>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb); });
+                             [&](uint32_t) { if (obs_t) emit_obs<N, TIGHT, kStoreThroughWhole>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb); });
       legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(a.sk_mode == 2 ? forb : 0u);
     }
     const size_t sb = (size_t)slice * a.B;
@@ -1390,7 +1390,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       if (a.rew) *(float2*)(a.rew + 2 * e) = skip ? make_float2(0.f, 0.f) : make_float2(rew0, rew1);
       if (a.term) a.term[e] = (uint8_t)((!skip && flag) ? 1 : 0);
     }
-    emit_outputs<N, TIGHT>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
+    emit_outputs<N, TIGHT, kStoreThroughWhole>(L, R, legal, m.wtm, wave, a.B, a.mask ? a.mask + sb * a.mask_pitch : nullptr, a.mask_pitch,
                     (!SK && a.obs) ? a.obs + sb * a.obs_pitch : nullptr, a.obs_pitch, lds_mask_all[wib], lds_obs_all[wib], lut, a.wb);
     wave_lds_fence();
     slice = slice + 1 == a.slices ? 0 : slice + 1;
@@ -1642,6 +1642,8 @@ struct pgxgo_ctx {
   uint8_t* obs_out;
   float* rew_out;
   uint8_t* term_out;
+  const uint8_t* mask_written;   // the buffers the last step (or bind) call wrote mask and observation to
+  const uint8_t* obs_written;
   uint2* zt;     // positional superko: per-game key tables, or null when the rule is off
   uint4* zcur;   // key and stone counts of every game's current position
   int sk_mode;   // 0 off, 1 enforced when the move is played, 2 honoured by the legal mask
@@ -1669,15 +1671,22 @@ unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + 
 // Boards per wavefront for the step and rollout launches.  A wavefront can hold W boards; with few games it is
 // better to spread them over more wavefronts (shorter floods, fewer output rounds per wavefront), so the count
 // grows with the batch until about two wavefronts per SIMD exist.
-// Output bytes of one ply from which the vector stores carry the non-temporal hint: measured at 19x19 with the
-// observation, the hint costs 20-30 % up to ~50 k games (everything still fits the 256 MB memory-side cache together
-// with the state) and gains 9-17 % from ~57 k games on.
-constexpr size_t kNonTemporalFrom = (size_t)350 << 20;
-// ... and up to which they are written through the L2 (measured at 19x19 with the observation: 6-12 % faster for 1024
-// to 6144 games, even at 8192 games = 53 MB, slower beyond).  The rollout kernel uses plain stores at every size (both
-// other kinds were measured slower there).
-constexpr size_t kWriteThroughUpTo = (size_t)48 << 20;
-int store_kind_for(size_t out_bytes) { return out_bytes > kNonTemporalFrom ? kStoreStream : (out_bytes <= kWriteThroughUpTo ? kStoreThrough : kStorePlain); }
+// Kind of the output stores of a one-launch-per-ply kernel by the bytes the launch writes, measured at 19x19 with the
+// observation: up to 32 MB (4096 games) everything written through the L2 is fastest (7.97 / 8.93 / 10.2 us per ply for
+// 1024 / 2048 / 4096 games against 8.5 / 10.2 / 11.4 us with plain stores); from there to the size of the memory-side
+// cache write-through for whole lines only (16384 games: 20.7 against 22.1 us); beyond it, where the hint costs
+// 20-30 % below ~50 k games and gains 9-17 % above ~57 k, the non-temporal hint on top (65536 games: 88 us against
+// 110 us plain).  The rollout kernel uses kStoreThroughWhole at every size (16384 games: 14.4 against 16.5 us per ply,
+// 65536 games: 53.8 against 60.2 us; the non-temporal hint is slower there at every size).
+// in_place: the launch overwrites the buffers the previous one wrote, whose lines are then still in the memory-side
+// cache.  In the middle range a launch into other buffers (a caller that records a trajectory) is faster with plain
+// stores (16384 games, line-padded pitches: 24.1 against 25.6 us per ply).
+constexpr size_t kWriteThroughUpTo = (size_t)32 << 20, kNonTemporalFrom = (size_t)350 << 20;
+int store_kind_for(size_t out_bytes, bool in_place) {
+  if (out_bytes <= kWriteThroughUpTo) return kStoreThrough;
+  if (out_bytes <= kNonTemporalFrom) return in_place ? kStoreThroughWhole : kStorePlain;
+  return kStoreStreamWhole;
+}
 size_t output_bytes_per_ply(const pgxgo_ctx* h, bool with_mask, bool with_obs) {
   return (size_t)h->B * ((with_mask ? (size_t)h->mask_pitch : 0) + (with_obs ? (size_t)h->obs_pitch : 0));
 }
@@ -1723,21 +1732,31 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   // bytes one ply touches: state rows + outputs; 256 MB of memory-side cache on this part, keep a margin
   const size_t touched = (size_t)h->B * (Geo<N>::row_bytes * N + (h->mask_out ? (size_t)h->mask_pitch : 0) + (h->obs_out ? (size_t)h->obs_pitch : 0));
   a.sparse_store = touched < ((size_t)192 << 20) ? 1 : 0;
-  a.store_kind = store_kind_for(output_bytes_per_ply(h, h->mask_out != nullptr, h->obs_out != nullptr));
+  a.store_kind = store_kind_for(output_bytes_per_ply(h, h->mask_out != nullptr, h->obs_out != nullptr),
+                                h->mask_out == h->mask_written && h->obs_out == h->obs_written);
+  h->mask_written = h->mask_out; h->obs_written = h->obs_out;
   const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
     if (!sample) a.next_actions = nullptr;
-    if (tight) hipLaunchKernelGGL((go_step_superko_kernel<N, true>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
-    else hipLaunchKernelGGL((go_step_superko_kernel<N, false>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+    auto sk = [&](auto tight_c) {
+      constexpr bool T = decltype(tight_c)::value;
+      if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThrough>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+      else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThroughWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+      else if (a.store_kind == kStorePlain) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStorePlain>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+      else hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreStreamWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+    };
+    if (tight) sk(std::true_type{});
+    else sk(std::false_type{});
     HIPCHK(hipGetLastError());
     return PGXGO_OK;
   }
   auto go = [&](auto sample_c, auto tight_c) {
     constexpr bool S = decltype(sample_c)::value, T = decltype(tight_c)::value;
-    if (a.store_kind == kStoreStream) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreStream>), grid, block, 0, h->stream, a);
-    else if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThrough>), grid, block, 0, h->stream, a);
-    else hipLaunchKernelGGL((go_step_kernel<N, S, T, kStorePlain>), grid, block, 0, h->stream, a);
+    if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThrough>), grid, block, 0, h->stream, a);
+    else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThroughWhole>), grid, block, 0, h->stream, a);
+    else if (a.store_kind == kStorePlain) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStorePlain>), grid, block, 0, h->stream, a);
+    else hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreStreamWhole>), grid, block, 0, h->stream, a);
   };
   if (sample && tight) go(std::true_type{}, std::true_type{});
   else if (sample) go(std::true_type{}, std::false_type{});
@@ -1777,9 +1796,9 @@ int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
   const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
   const size_t out_bytes = (size_t)a.n * ((a.mask ? (size_t)a.mask_pitch : 0) + (a.obs ? (size_t)a.obs_pitch : 0));
   if (tight && sk) hipLaunchKernelGGL((go_step_slots_kernel<N, true, true>), grid, block, 0, h->stream, a);
-  else if (tight && store_kind_for(out_bytes) == kStoreStream) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreStream>), grid, block, 0, h->stream, a);
-  else if (tight && store_kind_for(out_bytes) == kStoreThrough) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThrough>), grid, block, 0, h->stream, a);
-  else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes, true) == kStoreThrough) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThrough>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes, true) == kStoreThroughWhole) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThroughWhole>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreStreamWhole>), grid, block, 0, h->stream, a);
   else if (sk) hipLaunchKernelGGL((go_step_slots_kernel<N, false, true>), grid, block, 0, h->stream, a);
   else hipLaunchKernelGGL((go_step_slots_kernel<N, false, false>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
@@ -1853,6 +1872,7 @@ int fill_ctx(pgxgo_ctx* h, int32_t batch, int32_t board_size, uint32_t seed, con
   h->rew_int = (float*)(base + off_rew);
   h->term_int = base + off_term;
   h->mask_out = nullptr; h->obs_out = nullptr; h->rew_out = h->rew_int; h->term_out = h->term_int;
+  h->mask_written = nullptr; h->obs_written = nullptr;
   return PGXGO_OK;
 }
 
@@ -1948,6 +1968,7 @@ int pgxgo_bind_outputs(pgxgo_t h, uint8_t* mask_dev, uint8_t* obs_dev, float* re
   if (new_term != h->term_out) HIPCHK(hipMemcpyAsync(new_term, h->term_out, (size_t)h->B, hipMemcpyDeviceToDevice, h->stream));
   h->rew_out = new_rew; h->term_out = new_term;
   h->mask_out = mask_dev; h->obs_out = obs_dev;
+  h->mask_written = mask_dev; h->obs_written = obs_dev;
   if (mask_dev || obs_dev) return DISPATCH_N(h, launch_emit<19>(h, mask_dev, obs_dev), launch_emit<9>(h, mask_dev, obs_dev));
   return PGXGO_OK;
 }

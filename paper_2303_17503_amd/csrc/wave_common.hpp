@@ -65,25 +65,31 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
   __syncthreads();
 }
 
-// The 16-byte output stores, three kinds:
-//   kStorePlain   ordinary store (write-back in the compute die's L2);
-//   kStoreStream  with the non-temporal hint, for launches that write far more than the memory-side cache holds
-//                 (below that size it is slower);
-//   kStoreThrough written through the L2 to the memory-side level (`sc1`).  Lines left dirty in the L2 have to be
-//                 written back when the kernel ends: a plain fill of 106 MB pays 1.3 of its 16.8 us for that.  It pays
-//                 for launches that write up to ~48 MB and for streams made of whole 128-byte lines whose buffers
-//                 stay in the memory-side cache; for larger ragged streams and for buffers that have to reach DRAM
-//                 it is slower than the plain store (all measured).
+// The 16-byte output stores.  Basic kinds:
+//   kStorePlain          ordinary store (write-back in the compute die's L2);
+//   kStoreStream         with the non-temporal hint, for launches that write far more than the memory-side cache
+//                        holds (below that size it is slower);
+//   kStoreThrough        written through the L2 to the memory-side level (`sc1`).  Lines left dirty in the L2 have to
+//                        be written back when the kernel ends: a plain fill of 106 MB pays 1.3 of its 16.8 us for
+//                        that.  Partial lines written this way are expensive, though;
+//   kStoreStreamThrough  both modifiers.
+// and two that emit_bytes resolves per store instruction: the instructions of a stream that cover whole 128-byte
+// lines only (all but its first and its last two) / the others, whose lines are shared with the streams next door:
+//   kStoreThroughWhole   kStoreThrough / kStorePlain
+//   kStoreStreamWhole    kStoreStreamThrough / kStoreStream
+// Which kind a launch uses is decided on the host from the bytes it writes (all choices measured).
 // The compiler has no builtin for a 16-byte store with the `sc1` modifier, hence the instruction itself; the wait
 // state after it is the one the hardware asks for between a store of more than 8 bytes and a write to its data
 // registers.
-constexpr int kStorePlain = 0, kStoreStream = 1, kStoreThrough = 2;
+constexpr int kStorePlain = 0, kStoreStream = 1, kStoreThrough = 2, kStoreThroughWhole = 3, kStoreStreamThrough = 4, kStoreStreamWhole = 5;
 template <int KIND>
 __device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
   typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
   const vec4u v4 = {lo.x, lo.y, hi.x, hi.y};
+  static_assert(KIND != kStoreThroughWhole && KIND != kStoreStreamWhole, "resolved by emit_bytes");
   if constexpr (KIND == kStorePlain) *p = make_uint4(lo.x, lo.y, hi.x, hi.y);
   else if constexpr (KIND == kStoreStream) __builtin_nontemporal_store(v4, (vec4u*)p);
+  else if constexpr (KIND == kStoreStreamThrough) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v4) : "memory");
   else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(v4) : "memory");
 }
 
@@ -105,6 +111,8 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   // without per-lane tests (the choice is the same for the whole wavefront).
   const bool full_mid = m1 + q >= 64u * (uint32_t)(ROUNDS > 2 ? ROUNDS - 2 : 0);
   auto active = [&](int i) { return mine + 64 * i >= (int32_t)m0 && mine + 64 * i < (int32_t)m1; };
+  constexpr int ST_WHOLE = ST == kStoreThroughWhole ? kStoreThrough : (ST == kStoreStreamWhole ? kStoreStreamThrough : ST);
+  constexpr int ST_EDGE = ST == kStoreThroughWhole ? kStorePlain : (ST == kStoreStreamWhole ? kStoreStream : ST);
   if (full_mid) {
 #pragma unroll
     for (int g = 0; g < ROUNDS; g += GROUP) {
@@ -117,7 +125,8 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
 #pragma unroll
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
         const bool test = (i == 0 || i >= ROUNDS - 2);
-        if (!test || active(i)) store16<ST>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        if (!test) store16<ST_WHOLE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        else if (active(i)) store16<ST_EDGE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -129,7 +138,7 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i) v[i - g] = active(i) ? (uint32_t)src[64 * i] : 0u;
 #pragma unroll
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i)
-        if (active(i)) store16<ST>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        if (active(i)) store16<ST_EDGE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
