@@ -1605,7 +1605,7 @@ __global__ void lane_shift_probe_kernel(const uint32_t* in, uint32_t* out) {
 // buffers the step kernel writes) and an empty kernel (the gap between dependent launches on one stream).
 __global__ void __launch_bounds__(256) fill_probe_kernel(uint4* __restrict__ dst, size_t n16, uint32_t value) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte store per thread
-  if (i < n16) dst[i] = make_uint4(value, value, value, value);
+  if (i < n16) store16<kStoreThrough>(&dst[i], make_uint2(value, value), make_uint2(value, value));
 }
 __global__ void empty_probe_kernel() {}
 

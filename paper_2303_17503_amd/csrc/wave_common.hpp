@@ -113,6 +113,8 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
   auto active = [&](int i) { return mine + 64 * i >= (int32_t)m0 && mine + 64 * i < (int32_t)m1; };
   constexpr int ST_WHOLE = ST == kStoreThroughWhole ? kStoreThrough : (ST == kStoreStreamWhole ? kStoreStreamThrough : ST);
   constexpr int ST_EDGE = ST == kStoreThroughWhole ? kStorePlain : (ST == kStoreStreamWhole ? kStoreStream : ST);
+  // the round before the last lies completely inside the stream when the last one is not empty (the same in every lane)
+  const bool pen_whole = m1 + q >= 64u * (uint32_t)(ROUNDS - 1);
   if (full_mid) {
 #pragma unroll
     for (int g = 0; g < ROUNDS; g += GROUP) {
@@ -126,6 +128,7 @@ __device__ __forceinline__ void emit_bytes(const uint32_t* bits, const uint2* lu
       for (int i = g; i < g + GROUP && i < ROUNDS; ++i) {
         const bool test = (i == 0 || i >= ROUNDS - 2);
         if (!test) store16<ST_WHOLE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
+        else if (ST_WHOLE != ST_EDGE && i == ROUNDS - 2 && i > 0 && pen_whole) store16<ST_WHOLE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
         else if (active(i)) store16<ST_EDGE>(&out[64 * i], lut[v[i - g] & 255u], lut[v[i - g] >> 8]);
       }
       __builtin_amdgcn_sched_barrier(0);
