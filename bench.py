@@ -643,6 +643,17 @@ def ceilings(args, cfg):
         res["rollout_ms_per_ply_by_slices"][str(S)] = timed(lambda i: env.rollout(Lr, seed, pre + 20 + i * Lr, start_t=st.start, slices=S, **bufs),
                                                             max(1, K // Lr)) / Lr
         del bufs, env
+    # what the store path itself does to a plain fill of the same bytes: kind of store x alignment of a wavefront's 1 KB to 128-byte
+    # lines (base shifted by 16 bytes) x one buffer / rotating buffers
+    raw = [torch.empty(out_bytes // 16 * 16 + 256, dtype=torch.uint8, device="cuda") for _ in range(S_rot)]
+    res["fill_by_store_kind_ms"] = {}
+    for kind, kname in ((0, "ordinary"), (1, "non_temporal"), (2, "through_l2")):
+        for off in (0, 16):
+            v = [r[off: off + out_bytes // 16 * 16] for r in raw]
+            for x in v: pg.fill_probe(x, 1, kind)
+            res["fill_by_store_kind_ms"][f"{kname}_{'aligned' if off == 0 else 'shifted16'}"] = {
+                "in_place": timed(lambda i: pg.fill_probe(v[0], i, kind), 200), "rotating": timed(lambda i: pg.fill_probe(v[i % S_rot], i, kind), 200)}
+    del raw
     # the search-facing calls: B entries out of a pool of 2B games in the same regime, sources and destinations scattered over the pool
     pool = pg.GoEnv(2 * B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=True, line_padded=args.line_padded)
     pool.rollout(pre + 20, seed, 0, slices=1)

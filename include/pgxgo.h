@@ -219,10 +219,11 @@ int pgxgo_last_hip_error(void); /* hipError_t of the most recent PGXGO_EHIP on t
 
 /* Measurement helpers for the benchmark (no game logic).  pgxgo_fill_probe: one launch that fills nbytes (a multiple
  * of 16, dst_dev 16-byte aligned) with 16-byte vector stores of `value` -- the store-only ceiling the step kernel's
- * output rate is compared with.  The stores are written through the L2 like the step kernel's own (the faster of the
- * two ways to fill: 15.5 against 16.8 us for 106 MB with ordinary stores).  pgxgo_empty_probe: `count` back-to-back launches of an empty kernel, enqueued from
- * one host loop (the time per launch is the gap between dependent launches on one stream). */
-int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, void* stream);
+ * output rate is compared with.  kind: 0 ordinary stores, 1 with the non-temporal hint, 2 written through the L2 (what
+ * the kernels use for whole 128-byte lines; the fastest fill: 15.5 against 16.8 us for 106 MB); anything else is
+ * PGXGO_EINVAL.  pgxgo_empty_probe: `count` back-to-back launches of an empty kernel, enqueued from one host loop (the
+ * time per launch is the gap between dependent launches on one stream). */
+int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, int32_t kind, void* stream);
 int pgxgo_empty_probe(void* stream, int32_t count);
 
 /* Harness helper: cross-lane shift semantics of the target (lane i reads lane i-1 / i+1, zero at

@@ -37,7 +37,7 @@ def lib():
         L.pgxgo_bind_outputs.argtypes = [vp, vp, vp, vp, vp]
         L.pgxgo_set_output_buffers.argtypes = [vp, vp, vp, vp, vp]
         L.pgxgo_emit.argtypes = [vp, vp, vp]
-        L.pgxgo_fill_probe.argtypes = [vp, C.c_size_t, u32, vp]
+        L.pgxgo_fill_probe.argtypes = [vp, C.c_size_t, u32, i32, vp]
         L.pgxgo_empty_probe.argtypes = [vp, i32]
         L.pgxgo_step.argtypes = [vp, vp]
         L.pgxgo_random_actions.argtypes = [vp, u32, u32, vp, vp]
@@ -281,9 +281,10 @@ class GoEnv:
         _check(lib().pgxgo_import_state(self._h, *args), "pgxgo_import_state")
 
 
-def fill_probe(dst, value=0):
-    """One plain fill of the uint8 cuda tensor `dst` (16-byte aligned, size a multiple of 16) with 16-byte stores."""
-    _check(lib().pgxgo_fill_probe(_ptr(dst), dst.numel() * dst.element_size(), value & 0xFFFFFFFF,
+def fill_probe(dst, value=0, kind=2):
+    """One fill of the uint8 cuda tensor `dst` (16-byte aligned, size a multiple of 16) with 16-byte stores; kind: 0 ordinary,
+    1 non-temporal, 2 written through the L2."""
+    _check(lib().pgxgo_fill_probe(_ptr(dst), dst.numel() * dst.element_size(), value & 0xFFFFFFFF, int(kind),
                                   C.c_void_p(torch.cuda.current_stream().cuda_stream)), "pgxgo_fill_probe")
 
 

@@ -1603,9 +1603,10 @@ __global__ void lane_shift_probe_kernel(const uint32_t* in, uint32_t* out) {
 
 // Measurement helpers: a plain fill with 16-byte stores (the practical write ceiling of the machine on the same
 // buffers the step kernel writes) and an empty kernel (the gap between dependent launches on one stream).
+template <int ST>
 __global__ void __launch_bounds__(256) fill_probe_kernel(uint4* __restrict__ dst, size_t n16, uint32_t value) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte store per thread
-  if (i < n16) store16<kStoreThrough>(&dst[i], make_uint2(value, value), make_uint2(value, value));
+  if (i < n16) store16<ST>(&dst[i], make_uint2(value, value), make_uint2(value, value));
 }
 __global__ void empty_probe_kernel() {}
 
@@ -2143,12 +2144,15 @@ const char* pgxgo_strerror(int code) {
 
 int pgxgo_last_hip_error(void) { return g_last_hip; }
 
-int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, void* stream) {
-  if (!dst_dev || ((uintptr_t)dst_dev & 15u) != 0 || (nbytes & 15u) != 0) return PGXGO_EINVAL;
+int pgxgo_fill_probe(void* dst_dev, size_t nbytes, uint32_t value, int32_t kind, void* stream) {
+  if (!dst_dev || ((uintptr_t)dst_dev & 15u) != 0 || (nbytes & 15u) != 0 || kind < 0 || kind > 2) return PGXGO_EINVAL;
   if (nbytes == 0) return PGXGO_OK;
   const size_t n16 = nbytes / 16;
   if ((n16 + 255) / 256 > 0x7FFFFFFFull) return PGXGO_EINVAL;
-  hipLaunchKernelGGL(fill_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, (uint4*)dst_dev, n16, value);
+  const dim3 grid((unsigned)((n16 + 255) / 256)), block(256);
+  if (kind == 0) hipLaunchKernelGGL(fill_probe_kernel<kStorePlain>, grid, block, 0, (hipStream_t)stream, (uint4*)dst_dev, n16, value);
+  else if (kind == 1) hipLaunchKernelGGL(fill_probe_kernel<kStoreStream>, grid, block, 0, (hipStream_t)stream, (uint4*)dst_dev, n16, value);
+  else hipLaunchKernelGGL(fill_probe_kernel<kStoreThrough>, grid, block, 0, (hipStream_t)stream, (uint4*)dst_dev, n16, value);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }

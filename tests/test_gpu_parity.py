@@ -137,13 +137,16 @@ def test_fill_probe_fills_exactly_its_range():
     """The measurement helper stores through the same 16-byte store the kernels use for whole lines."""
     import paper_2303_17503_amd as pg
     raw = torch.full((1 << 20,), 7, dtype=torch.uint8, device="cuda")
-    for off, n in ((0, 16), (16, 4096), (48, 100000 * 16), (0, (1 << 20) - 64)):
-        raw.fill_(7)
-        pg.fill_probe(raw[off: off + n], 0x01020304)
-        torch.cuda.synchronize()
-        got = raw.cpu().numpy()
-        assert (got[:off] == 7).all() and (got[off + n:] == 7).all()
-        assert (got[off: off + n].view(np.uint32) == 0x01020304).all()
+    for kind in (0, 1, 2):
+        for off, n in ((0, 16), (16, 4096), (48, 100000 * 16), (0, (1 << 20) - 64)):
+            raw.fill_(7)
+            pg.fill_probe(raw[off: off + n], 0x01020304 + kind, kind=kind)
+            torch.cuda.synchronize()
+            got = raw.cpu().numpy()
+            assert (got[:off] == 7).all() and (got[off + n:] == 7).all()
+            assert (got[off: off + n].view(np.uint32) == 0x01020304 + kind).all()
+    with pytest.raises(pg.PgxGoError):
+        pg.fill_probe(raw[:64], 1, kind=3)
 
 
 def test_misaligned_output_base_pointers():
