@@ -1680,12 +1680,13 @@ unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + 
 // 110 us plain).  The rollout kernel uses kStoreThroughWhole at every size (16384 games: 14.4 against 16.5 us per ply,
 // 65536 games: 53.8 against 60.2 us; the non-temporal hint is slower there at every size).
 // in_place: the launch overwrites the buffers the previous one wrote, whose lines are then still in the memory-side
-// cache.  In the middle range a launch into other buffers (a caller that records a trajectory) is faster with plain
-// stores (16384 games, line-padded pitches: 24.1 against 25.6 us per ply).
+// cache.  In the middle range a launch into other buffers (a caller that records a trajectory) has to reach DRAM and
+// is faster with the hint as well (16384 games: 23.9 us per ply against 25.4 with ordinary stores and 25.9 with
+// write-through alone).
 constexpr size_t kWriteThroughUpTo = (size_t)32 << 20, kNonTemporalFrom = (size_t)350 << 20;
 int store_kind_for(size_t out_bytes, bool in_place) {
   if (out_bytes <= kWriteThroughUpTo) return kStoreThrough;
-  if (out_bytes <= kNonTemporalFrom) return in_place ? kStoreThroughWhole : kStorePlain;
+  if (out_bytes <= kNonTemporalFrom) return in_place ? kStoreThroughWhole : kStoreStreamWhole;
   return kStoreStreamWhole;
 }
 size_t output_bytes_per_ply(const pgxgo_ctx* h, bool with_mask, bool with_obs) {
@@ -1744,7 +1745,6 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
       constexpr bool T = decltype(tight_c)::value;
       if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThrough>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
       else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThroughWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
-      else if (a.store_kind == kStorePlain) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStorePlain>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
       else hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreStreamWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
     };
     if (tight) sk(std::true_type{});
@@ -1756,7 +1756,6 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
     constexpr bool S = decltype(sample_c)::value, T = decltype(tight_c)::value;
     if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThrough>), grid, block, 0, h->stream, a);
     else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreThroughWhole>), grid, block, 0, h->stream, a);
-    else if (a.store_kind == kStorePlain) hipLaunchKernelGGL((go_step_kernel<N, S, T, kStorePlain>), grid, block, 0, h->stream, a);
     else hipLaunchKernelGGL((go_step_kernel<N, S, T, kStoreStreamWhole>), grid, block, 0, h->stream, a);
   };
   if (sample && tight) go(std::true_type{}, std::true_type{});

@@ -499,6 +499,40 @@ def test_switching_output_buffers_and_the_combined_getter(N, B):
     assert (to_np(p.env.legal_mask()) == p.orc.legal_mask()).all()
 
 
+@pytest.mark.parametrize("line_padded", [False, True])
+def test_store_kinds_of_a_mid_size_batch(line_padded):
+    """The kind of the output stores follows the bytes a launch writes and whether it overwrites the previous launch's
+    buffers: 19x19 x 6001 games (39 MB per ply) in place, then rotating over three sets of buffers, then in place
+    again; sampled games against the oracle every ply, the whole batch against the getters (which use ordinary stores)."""
+    from gpu_common import to_np
+    import paper_2303_17503_amd as pg
+    N, B, seed = 19, 6001, 12
+    P = N * N
+    ids = np.unique(np.concatenate([np.arange(0, 12), np.arange(2990, 3010), np.arange(B - 9, B), np.random.default_rng(1).integers(0, B, 40)])).astype(np.int32)
+    env = pg.GoEnv(B, N, seed=seed, auto_reset=True, line_padded=line_padded)
+    orc = oracle.GoOracle(len(ids), N, seed=seed, auto_reset=True, env_ids=ids)
+    sel = torch.as_tensor(ids.astype(np.int64), device="cuda")
+    sets = [(env.new_mask().fill_(7), env.new_obs().fill_(7)) for _ in range(3)]
+    rew, term = torch.zeros((B, 2), device="cuda"), torch.zeros(B, dtype=torch.uint8, device="cuda")
+    env.bind_outputs(sets[0][0], sets[0][1], rew, term)
+    a = env.random_actions(seed, 0)
+    for t in range(45):
+        k = 0 if (t < 15 or t >= 36) else t % 3          # in place, rotating, in place
+        env.set_output_buffers(sets[k][0], sets[k][1], rew, term)
+        a_c = orc.random_actions(seed, t)
+        assert (to_np(a.index_select(0, sel)) == a_c).all(), t
+        a = env.step_sample(a, seed, t + 1)
+        orc.step(a_c)
+        m, o = sets[k]
+        assert (to_np(m.index_select(0, sel))[:, :P + 1] == orc.legal_mask()).all(), t
+        assert (to_np(env.obs_view(o).index_select(0, sel)) == orc.observe()).all(), t
+        assert to_np(rew.index_select(0, sel)).tobytes() == orc.rewards().tobytes(), t
+        if t % 7 == 0 or t >= 40:
+            assert torch.equal(env.legal_mask()[:, :P + 1], m[:, :P + 1]) and torch.equal(env.obs_view(env.observe()), env.obs_view(o)), t
+            if line_padded:
+                assert (m[:, P + 1:] == 0).all() and (o[:, P * 17:] == 0).all()
+
+
 @pytest.mark.parametrize("N,wb", [(19, 1), (19, 2), (19, 3), (9, 1), (9, 2), (9, 3), (9, 4), (9, 5), (9, 6)])
 def test_every_launch_shape(N, wb):
     """The number of boards a wavefront holds is a launch-shape choice: every value gives the oracle's results
