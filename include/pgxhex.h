@@ -118,8 +118,9 @@ int pgxhex_import_state(pgxhex_t h, const int8_t* board_dev, const int8_t* to_pl
                         const uint8_t* terminated_dev, const uint8_t* black_player_dev, const uint32_t* episode_dev);
 
 /* Launch-shape knob of pgxhex_step / pgxhex_step_sample / pgxhex_rollout: 1 = a board row per lane (5 boards per wavefront), 2 = a whole
- * board per lane (64 boards per wavefront; pays from about 200 k games on), 0 = the automatic choice by batch size.
- * Results do not depend on it.  Returns the mapping now in use (1 or 2), or a negative error code. */
+ * board per lane (64 boards per wavefront; pays from about 28 k games on, in the rollout kernel from about 20 k), 0 = the
+ * automatic choice by batch size.  Results do not depend on it.  Returns the mapping the step calls now use (1 or 2), or
+ * a negative error code. */
 int pgxhex_set_mapping(pgxhex_t h, int32_t mapping);
 
 /* Waits for the handle's stream. */

@@ -800,10 +800,14 @@ struct pgxhex_ctx {
 
 namespace {
 
-// From this many games on the one-launch-per-ply kernel holds a board per lane (four or more 64-board wavefronts per
-// SIMD exist then); below, a board row per lane, which needs far fewer games to fill the machine.
-constexpr int kLaneMappingFrom = 196608;
-bool board_per_lane(const pgxhex_ctx* h) { return h->mapping == 2 || (h->mapping == 0 && h->B >= kLaneMappingFrom); }
+// From this many games on the kernels hold a board per lane; below, a board row per lane, which needs far fewer games
+// to fill the machine.  Measured per ply, a board row per lane against a board per lane: one launch per ply 6.7 / 8.2 us
+// at 16384 games, 9.4 / 8.5 us at 32768, 14.1 / 11.0 us at 65536, 38.5 / 29.4 us at 262144; the rollout kernel
+// 4.4 / 4.95 us at 16384 games, 7.0 / 5.0 us at 32768, 12.5 / 5.5 us at 65536.
+constexpr int kLaneMappingFromStep = 28672, kLaneMappingFromRollout = 20480;
+bool board_per_lane(const pgxhex_ctx* h, bool rollout = false) {
+  return h->mapping == 2 || (h->mapping == 0 && h->B >= (rollout ? kLaneMappingFromRollout : kLaneMappingFromStep));
+}
 
 unsigned blocks_for(int B) {
   const unsigned waves = (unsigned)((B + W - 1) / W);
@@ -925,7 +929,7 @@ int pgxhex_rollout(pgxhex_t h, int32_t steps, int32_t slices, uint32_t seed, uin
   a.rows = h->rows; a.meta = h->meta; a.B = h->B; a.seed_env = h->seed; a.auto_reset = h->auto_reset;
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
-  if (board_per_lane(h))
+  if (board_per_lane(h, true))
     hipLaunchKernelGGL(hex_rollout_lane_kernel, dim3((unsigned)((h->B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock))), dim3(64 * kWavesPerBlock), 0,
                        h->stream, a);
   else hipLaunchKernelGGL(hex_rollout_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);

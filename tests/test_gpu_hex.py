@@ -138,7 +138,7 @@ def test_start_times_negative_zero_and_positive():
 @pytest.mark.parametrize("B", [1, 5, 63, 64, 65, 130, 333])
 @pytest.mark.parametrize("fused", [False, True])
 def test_board_per_lane_mapping(B, fused):
-    """The step kernels with a whole board per lane (the mapping used from ~200 k games on), forced at small ragged batches:
+    """The step kernels with a whole board per lane (the mapping used from ~28 k games on), forced at small ragged batches:
     full wavefronts, partly filled ones, several blocks; random play with auto-reset and staggered starts, every ply compared."""
     seed = 40 + B
     start = ((np.arange(B) * 7) % 30 - 3).astype(np.int32)
