@@ -690,10 +690,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   load_row<N>(a.planes, rows_total, L, R);
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
-  // loaded here and not where it is used: a load after the output stores would have to wait for them (one counter)
-  const bool wait_start = SAMPLE && L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
+  // loaded here and not where it is used: a load after the output stores would have to wait for them (one counter);
+  // looked at only after the table is filled, so that no wait for a load comes before the barrier
+  const int32_t start_raw = (SAMPLE && L.boardok && a.start_t) ? a.start_t[L.b] : INT32_MIN;
   fill_spread_table(lut);
   if (wave * a.wb >= a.B) return;   // whole wavefront idle; there is no block-wide barrier anywhere below
+  const bool wait_start = (int64_t)a.sample_t < (int64_t)held_back(start_raw);
   const RowWords W_loaded = row_words<N>(R);
   Meta m = unpack_meta(meta_raw);
 
@@ -802,6 +804,11 @@ __device__ __forceinline__ bool sk_real(uint2 e) { return (e.x | e.y) != 0u; }
 template <int N>
 __device__ __forceinline__ uint32_t sk_home(int colour, int count) {
   return (((uint32_t)(2 * count + colour + 1) * 0x9E3779B1u) >> (32 - Zt<N>::LOG2)) & ~(Zt<N>::WIN - 1u);
+}
+// the same for the play-time reading (mode 1), where a position has one entry, on the chain of its two stone counts
+template <int N>
+__device__ __forceinline__ uint32_t sk_home_counts(int nb, int nw) {
+  return (((uint32_t)((nb << 10) + nw + 1) * 0x9E3779B1u) >> (32 - Zt<N>::LOG2)) & ~(Zt<N>::WIN - 1u);
 }
 // Table accesses go to the device-coherent level: a wavefront of the rollout kernel reads in a later ply what its own
 // lanes wrote in an earlier one.
@@ -1115,9 +1122,66 @@ __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& 
   if constexpr (!EARLY) board_final(hdirty);
 }
 
+// The same for the reading in which the rule is looked at only for the move that is played (mode 1): no sets of
+// forbidden plays are kept, and a position has ONE table entry, on the chain of its two stone counts (so that it is
+// found whoever recreates it).  The position the requested play would give is known before the rules run -- it takes
+// exactly the opposing chains in atari next to it -- so its keys are looked up first; a hit turns the play into an
+// illegal action, otherwise the position goes into the chain's first free slot.  One table window read and one 8-byte
+// store per game-ply instead of three and two: what the rule costs is mostly these accesses to a table no cache
+// holds, which interrupt the stream of output writes in DRAM.  pre: the chain's first window for a play that takes
+// nothing, loaded by the caller as early as it can (home = ~0u: not loaded).
+template <int N, bool GATE, class Hook>
+__device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, Meta& m, SkGame& g, const Rules& rules, bool skip, bool want_pass,
+                                                  bool want_point, int pr_in, int pc_in, const uint2* tab_r, uint2* tab_w, uint2* zt, int game,
+                                                  uint32_t* scratch, float& rew0, float& rew1, bool& flag, const SkWin& pre, Hook&& board_final) {
+  const int c = m.wtm, own1 = (c ? g.nw : g.nb) + 1;
+  const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
+  Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
+  const uint32_t pbit = (L.valid && mv.playing && L.r == mv.pr) ? (1u << mv.pc) : 0u;
+  const uint32_t aopp = c ? R.ab : R.aw;
+  const uint32_t seed = dilate(pbit) & aopp;
+  int ncap = 0;
+  uint2 dk = make_uint2(0u, 0u);
+  if (__ballot(seed != 0u) != 0ull) {   // the play takes something (about one ply in ten)
+    const uint32_t taken = flood_plain(seed, aopp);
+    ncap = board_popcount<N>(L, taken);
+    dk = board_xor<N>(L, row_keys<N>(L.r, c ? taken : 0u, c ? 0u : taken), scratch);
+  }
+  const int opp1 = (c ? g.nb : g.nw) - ncap;
+  const int nb1 = c ? opp1 : own1, nw1 = c ? own1 : opp1;
+  const uint32_t kp = zkey((uint32_t)(mv.playing ? mv.pr * N + mv.pc : 0), (uint32_t)c);
+  const uint2 key = make_uint2(g.key.x ^ (c ? 0u : kp) ^ dk.x, g.key.y ^ (c ? kp : 0u) ^ dk.y);
+  bool hit = false, ok;
+  uint32_t free_slot;
+  sk_walk<N>(L, tab_r, sk_home_counts<N>(nb1, nw1), mv.playing, pre, ~0u,
+             [&](uint2 e, bool look) { if ((__ballot(look && e.x == key.x && e.y == key.y) & seg) != 0ull) hit = true; }, ok, free_slot);
+  if (mv.playing && hit) { mv.playing = false; mv.illegal = true; mv.pr = -100; mv.pc = 0; }
+  Rules r0 = rules;
+  r0.auto_reset = 0;   // the reset happens below, together with the table's
+  bool reset;
+  uint32_t captured, hdirty;
+  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+  const bool do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
+  if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }
+  board_final(hdirty);
+  if (mv.playing && !do_reset) {
+    if (L.valid && L.r == 0 && ok && sk_real(key)) tab_store(&tab_w[free_slot], key);
+    g.key = key; g.nb = nb1; g.nw = nw1;
+  }
+  if (do_reset) g = sk_fresh();
+  wave_mem_fence();
+  sk_clear_tables<N>(L, do_reset, zt, game);
+}
+// the window the next play of the game looks at first (mode 1), if that play takes nothing
+template <int N>
+__device__ __forceinline__ SkWin sk_window_play(const Lane<N>& L, const uint2* tab, const SkGame& g, const Meta& m, bool want) {
+  return sk_window<N>(L, tab, sk_home_counts<N>(g.nb + (m.wtm ? 0 : 1), g.nw + (m.wtm ? 1 : 0)), want);
+}
+
 // One ply with the repetition rule.  Same steps as go_step_kernel.
-template <int N, bool TIGHT, int ST>
-__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur, int mode) {
+// MODE: 1 = the rule is looked at when the move is played, 2 = honoured by the legal mask
+template <int N, bool TIGHT, int ST, int MODE>
+__global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel(StepArgs a, uint2* zt, uint4* zcur) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
@@ -1130,10 +1194,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   load_row<N>(a.planes, rows_total, L, R);
   const uint4 meta_raw = L.boardok ? a.meta[L.b] : make_uint4(0xFFFFFFFFu, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
-  SkGame g = L.boardok ? sk_unpack(zcur[L.b]) : sk_fresh();
-  const bool wait_start = a.next_actions && L.boardok && a.start_t && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
-  fill_spread_table(lut);
+  const uint4 g_raw = zcur[L.boardok ? L.b : 0];   // (an unconditional load: a conditional one is waited for on the spot)
+  const int32_t start_raw = (a.next_actions && L.boardok && a.start_t) ? a.start_t[L.b] : INT32_MIN;
+  fill_spread_table(lut);   // (nothing loaded above is looked at before this barrier)
   if (wave * a.wb >= a.B) return;
+  const bool wait_start = (int64_t)a.sample_t < (int64_t)held_back(start_raw);
+  SkGame g = L.boardok ? sk_unpack(g_raw) : sk_fresh();
   Meta m = unpack_meta(meta_raw);
   uint2* tab = zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
 
@@ -1142,24 +1208,32 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   const int pr = in_range ? act / N : 0, pc = in_range ? act - (act / N) * N : 0;
   SkWin none;
   none.home = ~0u; none.e = make_uint2(1u, 0u);
-  uint32_t forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
+  uint32_t forb = 0u;
   float rew0, rew1;
   bool flag;
-  sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
-                               false, none, [&](uint32_t) {   // a10, a11 (whole rows: writing only the changed planes gains nothing here)
-                                 if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
-                                 if (!skip) {
-                                   store_row<N>(a.planes, rows_total, L, R);
-                                   if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
-                                 }
-                               });
+  auto board_final = [&](uint32_t) {   // a10, a11 (whole rows: writing only the changed planes gains nothing here)
+    if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+    if (!skip) {
+      store_row<N>(a.planes, rows_total, L, R);
+      if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
+    }
+  };
+  if constexpr (MODE == 1) {
+    const SkWin pre = sk_window_play<N>(L, tab, g, m, !skip);
+    sk_step_core_play<N, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, pre,
+                               board_final);
+  } else {
+    forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
+    sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
+                                 false, none, board_final);
+    g.fw = sk_forb_word<N>(L, forb);
+  }
   if (!skip && L.valid && L.r == 0) {
     *(float2*)(a.rew + 2 * (size_t)L.b) = make_float2(rew0, rew1);
     a.term[L.b] = (uint8_t)(flag ? 1 : 0);
   }
-  g.fw = sk_forb_word<N>(L, forb);
 
-  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(mode == 2 ? forb : 0u);
+  const uint32_t legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(MODE == 2 ? forb : 0u);
   if (a.mask) emit_mask<N, TIGHT, ST>(L, legal, wave, a.B, a.mask, a.mask_pitch, lds_mask_all[wib], lut, a.wb);
   if (!skip && L.valid && L.r == 0) zcur[L.b] = sk_pack(g);
   if (a.next_actions) {
@@ -1171,7 +1245,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
 // Fills the tables from what the state still carries: the 8 history positions and the current one (set-up, import),
 // and finds the current position's forbidden plays.  The tables must have been cleared by an earlier launch.
 template <int N>
-__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, const uint4* meta, int B, uint2* zt, uint4* zcur) {
+__global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* planes, const uint4* meta, int B, uint2* zt, uint4* zcur, int mode) {
   __shared__ uint32_t scratch[64];
   const Lane<N> L(blockIdx.x, threadIdx.x, B);
   Row<N> R;
@@ -1197,19 +1271,20 @@ __global__ void __launch_bounds__(64) go_superko_rebuild_kernel(const uint4* pla
     g.key = board_xor<N>(L, k, scratch);
     g.nb = board_popcount<N>(L, black); g.nw = board_popcount<N>(L, white);
     const uint2 entry = g.key;
-    bool hit = false, ok_a, ok_b;
-    uint32_t free_a, free_b;
-    sk_walk<N>(L, tab, sk_home<N>(0, g.nb), L.boardok, none, ~0u, [&](uint2 e, bool look) { hit = hit || (look && e.x == entry.x && e.y == entry.y); },
-               ok_a, free_a);
+    bool hit = false, ok_a, ok_b = false;
+    uint32_t free_a, free_b = 0u;
+    // mode 1: one entry on the chain of the two counts; mode 2: one on the chain of each colour's count
+    sk_walk<N>(L, tab, mode == 1 ? sk_home_counts<N>(g.nb, g.nw) : sk_home<N>(0, g.nb), L.boardok, none, ~0u,
+               [&](uint2 e, bool look) { hit = hit || (look && e.x == entry.x && e.y == entry.y); }, ok_a, free_a);
     const bool found = board_any(hit, L.seglo, L.seghi) || !sk_real(entry);   // the empty board is never stored
-    sk_walk<N>(L, tab, sk_home<N>(1, g.nw), L.boardok && !found, none, ok_a ? free_a : ~0u, [](uint2, bool) {}, ok_b, free_b);
+    if (mode != 1) sk_walk<N>(L, tab, sk_home<N>(1, g.nw), L.boardok && !found, none, ok_a ? free_a : ~0u, [](uint2, bool) {}, ok_b, free_b);
     if (L.valid && L.r == 0) {
       if (!found && ok_a) tab_store(&tab[free_a], entry);
       if (!found && ok_b) tab_store(&tab[free_b], entry);
     }
     __threadfence();   // the next round's look-ups must see these inserts
   }
-  g.fw = sk_forb_word<N>(L, sk_forbidden<N>(L, tab, g, R, m, L.boardok, none, scratch));
+  if (mode != 1) g.fw = sk_forb_word<N>(L, sk_forbidden<N>(L, tab, g, R, m, L.boardok, none, scratch));
   if (L.valid && L.r == 0) zcur[L.b] = sk_pack(g);
 }
 
@@ -1241,7 +1316,7 @@ struct SlotArgs {
 };
 
 // SK: the positional-superko rule is on; a game that moves to another slot takes its key table along.
-template <int N, bool TIGHT, bool SK, int ST = kStorePlain>
+template <int N, bool TIGHT, int SK, int ST = kStorePlain>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots_kernel(SlotArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -1290,12 +1365,19 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
     __threadfence();   // the copied tables are in place before entries are added to them or they are cleared
     SkWin none;
     none.home = ~0u; none.e = make_uint2(1u, 0u);
-    forb = sk_forb_loaded<N>(L, tab_r, g, R, m, none, lds_mask_all[wib]);
-    sk_step_core<N, true, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, false,
-                          none, [&](uint32_t) { if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut); });
-    g.fw = sk_forb_word<N>(L, forb);
+    auto board_final = [&](uint32_t) { if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut); };
+    if constexpr (SK == 1) {
+      const SkWin pre = sk_window_play<N>(L, tab_r, g, m, !skip);
+      sk_step_core_play<N, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, pre,
+                                 board_final);
+    } else {
+      forb = sk_forb_loaded<N>(L, tab_r, g, R, m, none, lds_mask_all[wib]);
+      sk_step_core<N, true, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag,
+                                  false, none, board_final);
+      g.fw = sk_forb_word<N>(L, forb);
+    }
     if (L.valid && L.r == 0) a.zcur[dslot] = sk_pack(g);
-    if (a.sk_mode != 2) forb = 0u;   // the mask shows the simple-ko set unless the rule proper is on
+    if constexpr (SK != 2) forb = 0u;   // the mask shows the simple-ko set unless the rule proper is on
   }
   if ((threadIdx.x & 63) == L.j * G::STRIDE + 1 && L.j < G::W && L.b < a.n) {   // row-0 lane of the entry, inert or not
     if (bad) { if (a.term) a.term[L.b] = 255; }
@@ -1337,7 +1419,8 @@ struct RolloutArgs {
   int sk_mode;
 };
 
-template <int N, bool TIGHT, bool SK>
+// SK: 0 = simple ko only, 1 / 2 = positional superko at play time / in the legal mask
+template <int N, bool TIGHT, int SK>
 __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_kernel(RolloutArgs a) {
   using G = Geo<N>;
   __shared__ __attribute__((aligned(16))) uint32_t lds_obs_all[kWavesPerBlock][G::W * G::OBS_DW];
@@ -1363,9 +1446,13 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
     tab = a.zt + (size_t)(L.boardok ? L.b : 0) * Zt<N>::SLOTS;
     SkWin none;
     none.home = ~0u; none.e = make_uint2(1u, 0u);
-    forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
-    if (a.sk_mode == 2) legal &= ~forb;
+    if constexpr (SK != 1) forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
+    if constexpr (SK == 2) legal &= ~forb;
   }
+  // mode 1: the window the next ply looks at, loaded one ply ahead
+  SkWin ahead;
+  ahead.home = ~0u; ahead.e = make_uint2(1u, 0u);
+  if constexpr (SK == 1) ahead = sk_window_play<N>(L, tab, g, m, L.boardok);
   int slice = 0;
   for (int i = 0; i < a.steps; ++i) {   // the same trip count for every wavefront
     const uint32_t t = a.t0 + (uint32_t)i;
@@ -1381,9 +1468,18 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
       SkWin none;
       none.home = ~0u; none.e = make_uint2(1u, 0u);
       uint8_t* const obs_t = a.obs ? a.obs + (size_t)slice * a.B * a.obs_pitch : nullptr;
-      sk_step_core<N, false, true>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false, none,
-                             [&](uint32_t) { if (obs_t) emit_obs<N, TIGHT, kStoreThroughWhole>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb); });
-      legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(a.sk_mode == 2 ? forb : 0u);
+      auto board_final = [&](uint32_t) {
+        if (obs_t) emit_obs<N, TIGHT, kStoreThroughWhole>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+      };
+      if constexpr (SK == 1) {
+        sk_step_core_play<N, false>(L, R, m, g, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, ahead,
+                                    board_final);
+        ahead = sk_window_play<N>(L, tab, g, m, L.boardok);
+      } else {
+        sk_step_core<N, false, true>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false,
+                                     none, board_final);
+      }
+      legal = legal_row<N>(L, R, m.wtm, m.ko) & ~(SK == 2 ? forb : 0u);
     }
     const size_t sb = (size_t)slice * a.B;
     if (L.valid && L.r == 0) {
@@ -1401,7 +1497,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
   store_row<N>(a.planes, rows_total, L, R);
   if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
   if constexpr (SK) {
-    g.fw = sk_forb_word<N>(L, forb);
+    if constexpr (SK != 1) g.fw = sk_forb_word<N>(L, forb);
     if (L.valid && L.r == 0) a.zcur[L.b] = sk_pack(g);
   }
 }
@@ -1744,14 +1840,19 @@ int launch_step(pgxgo_ctx* h, const int32_t* actions, bool sample, uint32_t seed
   const bool tight = tight_pitches<N>(h);
   if (h->zt) {
     if (!sample) a.next_actions = nullptr;
-    auto sk = [&](auto tight_c) {
+    auto sk = [&](auto tight_c, auto mode_c) {
       constexpr bool T = decltype(tight_c)::value;
-      if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThrough>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
-      else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThroughWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
-      else hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreStreamWhole>), grid, block, 0, h->stream, a, h->zt, h->zcur, h->sk_mode);
+      constexpr int M = decltype(mode_c)::value;
+      if (a.store_kind == kStoreThrough) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThrough, M>), grid, block, 0, h->stream, a, h->zt, h->zcur);
+      else if (a.store_kind == kStoreThroughWhole) hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreThroughWhole, M>), grid, block, 0, h->stream, a, h->zt, h->zcur);
+      else hipLaunchKernelGGL((go_step_superko_kernel<N, T, kStoreStreamWhole, M>), grid, block, 0, h->stream, a, h->zt, h->zcur);
     };
-    if (tight) sk(std::true_type{});
-    else sk(std::false_type{});
+    using M1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    if (tight && h->sk_mode == 1) sk(std::true_type{}, M1{});
+    else if (tight) sk(std::true_type{}, M2{});
+    else if (h->sk_mode == 1) sk(std::false_type{}, M1{});
+    else sk(std::false_type{}, M2{});
     HIPCHK(hipGetLastError());
     return PGXGO_OK;
   }
@@ -1785,10 +1886,12 @@ template <int N>
 int launch_rollout(pgxgo_ctx* h, const RolloutArgs& a) {
   const dim3 grid(blocks_for_wb(h->B, h->wb)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
-  if (tight && sk) hipLaunchKernelGGL((go_rollout_kernel<N, true, true>), grid, block, 0, h->stream, a);
-  else if (tight) hipLaunchKernelGGL((go_rollout_kernel<N, true, false>), grid, block, 0, h->stream, a);
-  else if (sk) hipLaunchKernelGGL((go_rollout_kernel<N, false, true>), grid, block, 0, h->stream, a);
-  else hipLaunchKernelGGL((go_rollout_kernel<N, false, false>), grid, block, 0, h->stream, a);
+  if (tight && sk && h->sk_mode == 1) hipLaunchKernelGGL((go_rollout_kernel<N, true, 1>), grid, block, 0, h->stream, a);
+  else if (tight && sk) hipLaunchKernelGGL((go_rollout_kernel<N, true, 2>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_rollout_kernel<N, true, 0>), grid, block, 0, h->stream, a);
+  else if (sk && h->sk_mode == 1) hipLaunchKernelGGL((go_rollout_kernel<N, false, 1>), grid, block, 0, h->stream, a);
+  else if (sk) hipLaunchKernelGGL((go_rollout_kernel<N, false, 2>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_rollout_kernel<N, false, 0>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1798,12 +1901,14 @@ int launch_slots(pgxgo_ctx* h, const SlotArgs& a) {
   const dim3 grid(blocks_for<N>(a.n)), block(64 * kWavesPerBlock);
   const bool tight = tight_pitches<N>(h), sk = h->zt != nullptr;
   const size_t out_bytes = (size_t)a.n * ((a.mask ? (size_t)a.mask_pitch : 0) + (a.obs ? (size_t)a.obs_pitch : 0));
-  if (tight && sk) hipLaunchKernelGGL((go_step_slots_kernel<N, true, true>), grid, block, 0, h->stream, a);
-  else if (tight && store_kind_for(out_bytes, true) == kStoreThrough) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThrough>), grid, block, 0, h->stream, a);
-  else if (tight && store_kind_for(out_bytes, true) == kStoreThroughWhole) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreThroughWhole>), grid, block, 0, h->stream, a);
-  else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, false, kStoreStreamWhole>), grid, block, 0, h->stream, a);
-  else if (sk) hipLaunchKernelGGL((go_step_slots_kernel<N, false, true>), grid, block, 0, h->stream, a);
-  else hipLaunchKernelGGL((go_step_slots_kernel<N, false, false>), grid, block, 0, h->stream, a);
+  if (tight && sk && h->sk_mode == 1) hipLaunchKernelGGL((go_step_slots_kernel<N, true, 1>), grid, block, 0, h->stream, a);
+  else if (tight && sk) hipLaunchKernelGGL((go_step_slots_kernel<N, true, 2>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes, true) == kStoreThrough) hipLaunchKernelGGL((go_step_slots_kernel<N, true, 0, kStoreThrough>), grid, block, 0, h->stream, a);
+  else if (tight && store_kind_for(out_bytes, true) == kStoreThroughWhole) hipLaunchKernelGGL((go_step_slots_kernel<N, true, 0, kStoreThroughWhole>), grid, block, 0, h->stream, a);
+  else if (tight) hipLaunchKernelGGL((go_step_slots_kernel<N, true, 0, kStoreStreamWhole>), grid, block, 0, h->stream, a);
+  else if (sk && h->sk_mode == 1) hipLaunchKernelGGL((go_step_slots_kernel<N, false, 1>), grid, block, 0, h->stream, a);
+  else if (sk) hipLaunchKernelGGL((go_step_slots_kernel<N, false, 2>), grid, block, 0, h->stream, a);
+  else hipLaunchKernelGGL((go_step_slots_kernel<N, false, 0>), grid, block, 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXGO_OK;
 }
@@ -1838,7 +1943,7 @@ int launch_superko_refresh(pgxgo_ctx* h, bool rebuild) {
   hipLaunchKernelGGL(go_zero_kernel, dim3(blocks), dim3(256), 0, h->stream, (uint4*)h->zt, n16);
   HIPCHK(hipGetLastError());
   if (rebuild) {
-    hipLaunchKernelGGL(go_superko_rebuild_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, h->zt, h->zcur);
+    hipLaunchKernelGGL(go_superko_rebuild_kernel<N>, dim3(waves_for<N>(h->B)), dim3(64), 0, h->stream, h->planes, h->meta, h->B, h->zt, h->zcur, h->sk_mode);
     HIPCHK(hipGetLastError());
   }
   return PGXGO_OK;

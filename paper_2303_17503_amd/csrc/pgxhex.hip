@@ -283,9 +283,10 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
   const int act = L.boardok ? a.actions[L.b] : -1;
   // loaded with the state: a load issued after the output stores would have to wait for them (one counter)
-  const bool wait_start = SAMPLE && a.start_t && L.boardok && (int64_t)a.sample_t < (int64_t)a.start_t[L.b];
+  const int32_t start_raw = (SAMPLE && a.start_t && L.boardok) ? a.start_t[L.b] : INT32_MIN;
   fill_spread_table(lut);
   if (wave * W >= a.B) return;
+  const bool wait_start = (int64_t)a.sample_t < (int64_t)held_back(start_raw);
 
   uint32_t bk = word & 0xFFFFu, wt = word >> 16;
   Meta m = unpack_meta(mv);
@@ -545,10 +546,11 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
   const uint4 mv = ok ? a.meta[b] : make_uint4(0u, 0u, 0u, 0u);
   const int act = ok ? a.actions[b] : -1;
   // loaded with the state: a load issued after the output stores would have to wait for them (one counter)
-  const bool wait_start = SAMPLE && a.start_t && ok && (int64_t)a.sample_t < (int64_t)a.start_t[b];
+  const int32_t start_raw = (SAMPLE && a.start_t && ok) ? a.start_t[b] : INT32_MIN;
   fill_spread4_table(lut4);
-  fill_spread_table(lut);                   // ends with the block's only barrier
+  fill_spread_table(lut);                   // ends with the block's only barrier (nothing loaded above is looked at before it)
   if (b0 >= a.B) return;
+  const bool wait_start = (int64_t)a.sample_t < (int64_t)held_back(start_raw);
   const int nb = a.B - b0 < 64 ? a.B - b0 : 64;
   Meta m = unpack_meta(mv);
   B128 bk, wt;

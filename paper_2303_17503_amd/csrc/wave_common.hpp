@@ -42,6 +42,13 @@ __device__ __forceinline__ bool board_any(bool pred, uint32_t seglo, uint32_t se
   return (((uint32_t)m & seglo) | ((uint32_t)(m >> 32) & seghi)) != 0u;
 }
 
+// Returns v; keeps the compiler from evaluating anything that depends on a loaded value before this point (it
+// would otherwise move the first use, and with it the wait for the load, up to the load itself).
+__device__ __forceinline__ int32_t held_back(int32_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 // LDS traffic between the lanes of one wavefront needs no hardware barrier (a wavefront's LDS operations
 // execute in program order); this only keeps the compiler from moving accesses across the hand-over.
 __device__ __forceinline__ void wave_lds_fence() {
