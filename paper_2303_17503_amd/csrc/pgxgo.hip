@@ -1124,26 +1124,40 @@ __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& 
 
 // The same for the reading in which the rule is looked at only for the move that is played (mode 1): no sets of
 // forbidden plays are kept, and a position has ONE table entry, on the chain of its two stone counts (so that it is
-// found whoever recreates it).  The position the requested play would give is known before the rules run -- it takes
-// exactly the opposing chains in atari next to it -- so its keys are looked up first; a hit turns the play into an
-// illegal action, otherwise the position goes into the chain's first free slot.  One table window read and one 8-byte
-// store per game-ply instead of three and two: what the rule costs is mostly these accesses to a table no cache
-// holds, which interrupt the stream of output writes in DRAM.  pre: the chain's first window for a play that takes
-// nothing, loaded by the caller as early as it can (home = ~0u: not loaded).
-template <int N, bool GATE, class Hook>
+// found whoever recreates it).  One table window read and one 8-byte store per game-ply instead of three and two.
+// pre: the chain's first window for a play that takes nothing, loaded by the caller as early as it can (home = ~0u:
+// not loaded).  Two orders:
+//   POST = false (the rollout kernel, whose state lives in registers): the position the requested play would give is
+//     known before the rules run -- it takes exactly the opposing chains in atari next to it -- so its keys are looked
+//     up first; a hit turns the play into an illegal action.
+//   POST = true (one launch per ply, where every wavefront would wait for the window before it can do anything else):
+//     the rules run first, on the assumption that the play repeats nothing, and the look-up follows, when the window
+//     has long arrived; after a hit (rare) restore(R, m, which) brings back the state as loaded for the boards flagged
+//     and the ply is applied again as an illegal action.
+template <int N, bool GATE, bool POST, class Hook, class Restore>
 __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, Meta& m, SkGame& g, const Rules& rules, bool skip, bool want_pass,
                                                   bool want_point, int pr_in, int pc_in, const uint2* tab_r, uint2* tab_w, uint2* zt, int game,
-                                                  uint32_t* scratch, float& rew0, float& rew1, bool& flag, const SkWin& pre, Hook&& board_final) {
+                                                  uint32_t* scratch, float& rew0, float& rew1, bool& flag, const SkWin& pre, Hook&& board_final,
+                                                  Restore&& restore) {
   const int c = m.wtm, own1 = (c ? g.nw : g.nb) + 1;
   const uint64_t seg = ((uint64_t)L.seghi << 32) | L.seglo;
   Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
-  const uint32_t pbit = (L.valid && mv.playing && L.r == mv.pr) ? (1u << mv.pc) : 0u;
-  const uint32_t aopp = c ? R.ab : R.aw;
-  const uint32_t seed = dilate(pbit) & aopp;
+  Rules r0 = rules;
+  r0.auto_reset = 0;   // the reset happens below, together with the table's
+  bool reset;
+  uint32_t captured = 0u, hdirty = 0u;
+  if constexpr (POST) apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+  // the stones the play takes: known from the rules (POST), else the opposing chains in atari next to it
+  uint32_t taken = captured;
+  if constexpr (!POST) {
+    const uint32_t pbit = (L.valid && mv.playing && L.r == mv.pr) ? (1u << mv.pc) : 0u;
+    const uint32_t aopp = c ? R.ab : R.aw;
+    const uint32_t seed = dilate(pbit) & aopp;
+    if (__ballot(seed != 0u) != 0ull) taken = flood_plain(seed, aopp);
+  }
   int ncap = 0;
   uint2 dk = make_uint2(0u, 0u);
-  if (__ballot(seed != 0u) != 0ull) {   // the play takes something (about one ply in ten)
-    const uint32_t taken = flood_plain(seed, aopp);
+  if (__ballot(taken != 0u) != 0ull) {   // about one ply in ten
     ncap = board_popcount<N>(L, taken);
     dk = board_xor<N>(L, row_keys<N>(L.r, c ? taken : 0u, c ? 0u : taken), scratch);
   }
@@ -1155,12 +1169,21 @@ __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, M
   uint32_t free_slot;
   sk_walk<N>(L, tab_r, sk_home_counts<N>(nb1, nw1), mv.playing, pre, ~0u,
              [&](uint2 e, bool look) { if ((__ballot(look && e.x == key.x && e.y == key.y) & seg) != 0ull) hit = true; }, ok, free_slot);
-  if (mv.playing && hit) { mv.playing = false; mv.illegal = true; mv.pr = -100; mv.pc = 0; }
-  Rules r0 = rules;
-  r0.auto_reset = 0;   // the reset happens below, together with the table's
-  bool reset;
-  uint32_t captured, hdirty;
-  apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+  const bool repeats = mv.playing && hit;
+  if (repeats) { mv.playing = false; mv.illegal = true; mv.pr = -100; mv.pc = 0; }
+  if constexpr (!POST) {
+    apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+  } else if (__ballot(repeats) != 0ull) {
+    restore(R, m, repeats);   // the boards that repeat get the state as loaded back
+    Move again = mv;          // the other boards of the wavefront keep what the first pass gave them: for them, a skipped ply
+    if (!repeats) { again.skip = true; again.frozen = false; again.is_pass = false; again.playing = false; again.illegal = false; again.pr = -100; again.pc = 0; }
+    float a0, a1;
+    bool f2, rs2;
+    uint32_t cap2, hd2;
+    apply_move<N>(L, R, m, r0, again, a0, a1, f2, cap2, rs2, hd2);
+    if (repeats) { rew0 = a0; rew1 = a1; flag = f2; }
+    hdirty = ~0u;
+  }
   const bool do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
   if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }
   board_final(hdirty);
@@ -1220,8 +1243,12 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   };
   if constexpr (MODE == 1) {
     const SkWin pre = sk_window_play<N>(L, tab, g, m, !skip);
-    sk_step_core_play<N, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, pre,
-                               board_final);
+    sk_step_core_play<N, true, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, pre,
+                                     board_final, [&](Row<N>& Rr, Meta& mr, bool which) {   // nothing has been stored yet: memory holds the state as loaded
+                                       Row<N> T;
+                                       load_row<N>(a.planes, rows_total, L, T);
+                                       if (which) { Rr = T; mr = unpack_meta(meta_raw); }
+                                     });
   } else {
     forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
     sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
@@ -1368,8 +1395,14 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
     auto board_final = [&](uint32_t) { if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.n, a.obs, a.obs_pitch, lds_obs_all[wib], lut); };
     if constexpr (SK == 1) {
       const SkWin pre = sk_window_play<N>(L, tab_r, g, m, !skip);
-      sk_step_core_play<N, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, pre,
-                                 board_final);
+      sk_step_core_play<N, true, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag, pre,
+                                       board_final, [&](Row<N>& Rr, Meta& mr, bool which) {   // the source slot still holds the state as loaded
+                                         Lane<N> Ls = L;
+                                         Ls.slot = src;
+                                         Row<N> T;
+                                         load_row<N>(a.planes, rows_total, Ls, T);
+                                         if (which) { Rr = T; mr = unpack_meta(meta_raw); }
+                                       });
     } else {
       forb = sk_forb_loaded<N>(L, tab_r, g, R, m, none, lds_mask_all[wib]);
       sk_step_core<N, true, true>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab_r, tab_w, a.zt, dslot, lds_mask_all[wib], rew0, rew1, flag,
@@ -1472,8 +1505,8 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
         if (obs_t) emit_obs<N, TIGHT, kStoreThroughWhole>(L, R.h, m.wtm, wave, a.B, obs_t, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
       };
       if constexpr (SK == 1) {
-        sk_step_core_play<N, false>(L, R, m, g, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, ahead,
-                                    board_final);
+        sk_step_core_play<N, false, false>(L, R, m, g, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag,
+                                           ahead, board_final, [](Row<N>&, Meta&, bool) {});
         ahead = sk_window_play<N>(L, tab, g, m, L.boardok);
       } else {
         sk_step_core<N, false, true>(L, R, m, g, forb, a.rules, skip, d.pass, d.point, d.pr, d.pc, tab, tab, a.zt, L.b, lds_mask_all[wib], rew0, rew1, flag, false,
