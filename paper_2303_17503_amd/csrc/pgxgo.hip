@@ -1131,9 +1131,10 @@ __device__ __forceinline__ void sk_step_core(const Lane<N>& L, Row<N>& R, Meta& 
 //     known before the rules run -- it takes exactly the opposing chains in atari next to it -- so its keys are looked
 //     up first; a hit turns the play into an illegal action.
 //   POST = true (one launch per ply, where every wavefront would wait for the window before it can do anything else):
-//     the rules run first, on the assumption that the play repeats nothing, and the look-up follows, when the window
-//     has long arrived; after a hit (rare) restore(R, m, which) brings back the state as loaded for the boards flagged
-//     and the ply is applied again as an illegal action.
+//     the rules run first, on the assumption that the play repeats nothing, board_final() is called (the observation is
+//     under way), and the look-up follows; after a hit (rare) restore(R, m, which) brings back the state as loaded for
+//     the boards flagged, the ply is applied again as an illegal action and board_final() is called once more: the
+//     same wavefront overwrites what it stored the first time.
 template <int N, bool GATE, bool POST, class Hook, class Restore>
 __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, Meta& m, SkGame& g, const Rules& rules, bool skip, bool want_pass,
                                                   bool want_point, int pr_in, int pc_in, const uint2* tab_r, uint2* tab_w, uint2* zt, int game,
@@ -1144,9 +1145,16 @@ __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, M
   Move mv = gate_move<N, GATE>(L, R, m, skip, want_pass, want_point, pr_in, pc_in);
   Rules r0 = rules;
   r0.auto_reset = 0;   // the reset happens below, together with the table's
-  bool reset;
+  bool reset, do_reset = false;
   uint32_t captured = 0u, hdirty = 0u;
-  if constexpr (POST) apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+  if constexpr (POST) {
+    apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+    do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
+    if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }
+    // The window has to be in registers before the caller's stores are issued: loads and stores share one counter.
+    asm volatile("" ::"v"(pre.e.x), "v"(pre.e.y));
+    board_final(hdirty);   // on the assumption that nothing repeats; done again below if something does
+  }
   // the stones the play takes: known from the rules (POST), else the opposing chains in atari next to it
   uint32_t taken = captured;
   if constexpr (!POST) {
@@ -1173,6 +1181,9 @@ __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, M
   if (repeats) { mv.playing = false; mv.illegal = true; mv.pr = -100; mv.pc = 0; }
   if constexpr (!POST) {
     apply_move<N>(L, R, m, r0, mv, rew0, rew1, flag, captured, reset, hdirty);
+    do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
+    if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }
+    board_final(hdirty);
   } else if (__ballot(repeats) != 0ull) {
     restore(R, m, repeats);   // the boards that repeat get the state as loaded back
     Move again = mv;          // the other boards of the wavefront keep what the first pass gave them: for them, a skipped ply
@@ -1181,12 +1192,13 @@ __device__ __forceinline__ void sk_step_core_play(const Lane<N>& L, Row<N>& R, M
     bool f2, rs2;
     uint32_t cap2, hd2;
     apply_move<N>(L, R, m, r0, again, a0, a1, f2, cap2, rs2, hd2);
-    if (repeats) { rew0 = a0; rew1 = a1; flag = f2; }
-    hdirty = ~0u;
+    if (repeats) {
+      rew0 = a0; rew1 = a1; flag = f2;
+      do_reset = rules.auto_reset != 0;   // the illegal action has ended the game
+      if (do_reset) reset_board<N>(L, R, m, rules.seed);
+    }
+    board_final(~0u);
   }
-  const bool do_reset = !skip && !mv.frozen && m.term && rules.auto_reset != 0;
-  if (do_reset) { reset_board<N>(L, R, m, rules.seed); hdirty = ~0u; }
-  board_final(hdirty);
   if (mv.playing && !do_reset) {
     if (L.valid && L.r == 0 && ok && sk_real(key)) tab_store(&tab_w[free_slot], key);
     g.key = key; g.nb = nb1; g.nw = nw1;
@@ -1234,21 +1246,25 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   uint32_t forb = 0u;
   float rew0, rew1;
   bool flag;
-  auto board_final = [&](uint32_t) {   // a10, a11 (whole rows: writing only the changed planes gains nothing here)
-    if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+  auto store_state = [&]() {   // a11 (whole rows: writing only the changed planes gains nothing here)
     if (!skip) {
       store_row<N>(a.planes, rows_total, L, R);
       if (L.valid && L.r == 0) a.meta[L.b] = pack_meta(m);
     }
   };
+  auto board_final = [&](uint32_t) {   // a10, a11
+    if (a.obs) emit_obs<N, TIGHT, ST>(L, R.h, m.wtm, wave, a.B, a.obs, a.obs_pitch, lds_obs_all[wib], lut, a.wb);
+    if constexpr (MODE != 1) store_state();
+  };
   if constexpr (MODE == 1) {
     const SkWin pre = sk_window_play<N>(L, tab, g, m, !skip);
     sk_step_core_play<N, true, true>(L, R, m, g, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag, pre,
-                                     board_final, [&](Row<N>& Rr, Meta& mr, bool which) {   // nothing has been stored yet: memory holds the state as loaded
+                                     board_final, [&](Row<N>& Rr, Meta& mr, bool which) {   // the state is stored below: memory still holds it as loaded
                                        Row<N> T;
                                        load_row<N>(a.planes, rows_total, L, T);
                                        if (which) { Rr = T; mr = unpack_meta(meta_raw); }
                                      });
+    store_state();
   } else {
     forb = sk_forb_loaded<N>(L, tab, g, R, m, none, lds_mask_all[wib]);
     sk_step_core<N, true, false>(L, R, m, g, forb, a.rules, skip, act == G::P, in_range, pr, pc, tab, tab, zt, L.b, lds_mask_all[wib], rew0, rew1, flag,

@@ -85,9 +85,9 @@ __device__ __forceinline__ void fill_spread_table(uint2* lut) {
 //   kStoreThroughWhole   kStoreThrough / kStorePlain
 //   kStoreStreamWhole    kStoreStreamThrough / kStoreStream
 // Which kind a launch uses is decided on the host from the bytes it writes (all choices measured).
-// The compiler has no builtin for a 16-byte store with the `sc1` modifier, hence the instruction itself; the wait
-// state after it is the one the hardware asks for between a store of more than 8 bytes and a write to its data
-// registers.
+// The compiler has no builtin for a 16-byte store with the `sc1` modifier, hence the instruction itself.  It is
+// followed by the two wait states this hardware needs between a store of more than 8 bytes and a write to its data
+// registers (the compiler inserts them for its own stores; with one wait state rows of the state were stored wrong).
 constexpr int kStorePlain = 0, kStoreStream = 1, kStoreThrough = 2, kStoreThroughWhole = 3, kStoreStreamThrough = 4, kStoreStreamWhole = 5;
 template <int KIND>
 __device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
@@ -96,8 +96,8 @@ __device__ __forceinline__ void store16(uint4* p, uint2 lo, uint2 hi) {
   static_assert(KIND != kStoreThroughWhole && KIND != kStoreStreamWhole, "resolved by emit_bytes");
   if constexpr (KIND == kStorePlain) *p = make_uint4(lo.x, lo.y, hi.x, hi.y);
   else if constexpr (KIND == kStoreStream) __builtin_nontemporal_store(v4, (vec4u*)p);
-  else if constexpr (KIND == kStoreStreamThrough) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v4) : "memory");
-  else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(v4) : "memory");
+  else if constexpr (KIND == kStoreStreamThrough) asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" ::"v"(p), "v"(v4) : "memory");
+  else asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(p), "v"(v4) : "memory");
 }
 
 // MAXBYTES: upper bound of nbytes (fixes the number of rounds of 64 groups).  dst and nbytes must be the same in
