@@ -33,6 +33,10 @@
 //   * How many boards a launch puts into a wavefront (1 .. W) is chosen per launch: W for throughput at large
 //     batches, fewer at small batches where the slowest board of a wavefront and its serial output rounds
 //     decide the latency.
+//   * Output stores: every store instruction of a wavefront covers whole 128-byte lines (wave_common.hpp), and
+//     the kind of store -- through the L2, with the non-temporal hint, ordinary -- is chosen per launch from the
+//     bytes it writes and from whether it overwrites the previous launch's buffers (store_kind_for).  The
+//     line-padded output pitches make a wavefront's stream consist of whole lines only.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
