@@ -24,9 +24,9 @@ sys.path.insert(0, ROOT)
 
 
 class Args:
-    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0, seed=None, mapping=0):
+    def __init__(self, game="go", config=3, plies=0, threads=16, state_every=100, superko=False, rollout=0, seed=None, mapping=0, line_padded=False):
         self.game, self.config, self.plies, self.threads, self.state_every = game, config, plies, threads, state_every
-        self.superko, self.rollout, self.seed, self.mapping = superko, rollout, seed, mapping
+        self.superko, self.rollout, self.seed, self.mapping, self.line_padded = superko, rollout, seed, mapping, line_padded
 
 
 def main():
@@ -41,9 +41,10 @@ def main():
     ap.add_argument("--rollout", type=int, default=0, help="L > 0: use the rollout kernel, L plies per launch, every ply recorded in its own slice")
     ap.add_argument("--seed", type=int, default=None, help="another seed than the configuration's (more trajectories of the same shape)")
     ap.add_argument("--mapping", type=int, default=0, help="Hex only: 1 = a board row per lane, 2 = a board per lane, 0 = the library's choice")
+    ap.add_argument("--line-padded", action="store_true", help="Go only: output pitches rounded up to 128-byte lines (pad bytes must come out as zeros)")
     a = ap.parse_args()
     try:
-        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout, a.seed, a.mapping))
+        run(Args(a.game, a.config, a.plies, a.threads, a.state_every, a.superko, a.rollout, a.seed, a.mapping, a.line_padded))
     except AssertionError as e:
         print(e, flush=True)
         sys.exit(1)
@@ -69,7 +70,9 @@ def run(args):
     start = workloads.start_times(cfg) if go else None
     st_dev = None if start is None else torch.as_tensor(start, device="cuda")
 
-    env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset) if go else pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
+    assert go or not args.line_padded, "the line-padded layout is a Go option"
+    env = pg.GoEnv(B, N, seed=seed, komi_x2=cfg.komi_x2, auto_reset=cfg.auto_reset, line_padded=args.line_padded) if go else \
+        pg.HexEnv(B, seed=seed, auto_reset=cfg.auto_reset)
     if args.mapping:
         assert not go, "the mapping is a Hex launch-shape choice"
         assert env.set_mapping(args.mapping) == args.mapping
@@ -77,6 +80,8 @@ def run(args):
         assert go, "the superko rule is a Go option"
         env.enable_superko(int(args.superko))
     mask, obs = env.new_mask(), env.new_obs()
+    if args.line_padded:
+        mask.fill_(7); obs.fill_(7)     # the pad bytes belong to the records and have to come out as zeros
     rew = torch.zeros((B, 2), dtype=torch.float32, device="cuda")
     term = torch.zeros(B, dtype=torch.uint8, device="cuda")
     env.bind_outputs(mask, obs, rew, term)
@@ -114,6 +119,7 @@ def run(args):
         live = a >= 0
         if not (n_mask[lo:hi, :P + 1] == o.legal_mask()).all(): return f"mask, shard {k}"
         if not (n_obs[lo:hi, :P * planes].reshape(hi - lo, N, N, planes) == o.observe()).all(): return f"observation, shard {k}"
+        if args.line_padded and (n_mask[lo:hi, P + 1:][live].any() or n_obs[lo:hi, P * planes:][live].any()): return f"pad bytes, shard {k}"
         if not (n_rew[lo:hi][live] == o.rewards()[live]).all(): return f"rewards, shard {k}"
         if not (n_term[lo:hi][live] == o.terminated()[live]).all(): return f"terminated, shard {k}"
         if g_state is not None:
@@ -156,7 +162,7 @@ def run(args):
             env.step_sample(acts[t & 1], seed, t + 1, st_dev, out=acts[(t + 1) & 1])
             h_mask.copy_(mask); h_obs.copy_(obs); h_rew.copy_(rew); h_term.copy_(term)
             compare(t, with_state=(t % args.state_every == 0 or t == T - 1))
-    print(f"FULL PARITY OK: {cfg.name}{(' with superko (mode %d)' % int(args.superko)) if args.superko else ''}{' through the rollout kernel' if args.rollout else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
+    print(f"FULL PARITY OK: {cfg.name}{(' with superko (mode %d)' % int(args.superko)) if args.superko else ''}{' through the rollout kernel' if args.rollout else ''}{' with line-padded pitches' if args.line_padded else ''}, {B} environments x {T} launches = {n_plies} game-plies, every drawn action, mask, observation, "
           f"reward and terminated flag compared; state every {args.state_every} plies; {len(shards)} oracle shards; {time.time() - t0:.0f} s", flush=True)
     pool.shutdown()
     return n_plies

@@ -63,3 +63,11 @@ def test_every_environment_every_ply_through_the_rollout_kernel(game, config):
     plies = 800 if (game, config) == ("go", 3) else 0
     n = full_parity.run(full_parity.Args(game=game, config=config, rollout=8, plies=plies))
     assert n == (16384 * 800 if plies else EXPECTED[(game, config)])
+
+
+@pytest.mark.parametrize("config,rollout,plies", [(3, 0, 800), (2, 0, 0), (3, 8, 400)])
+def test_every_environment_every_ply_with_line_padded_pitches(config, rollout, plies):
+    """The layout bench.py --line-padded times: pitches of 6144 / 384 bytes, the pad bytes written as zeros; one launch per
+    ply (the headline batch and a small one) and the rollout kernel with every ply in its own slice."""
+    n = full_parity.run(full_parity.Args(game="go", config=config, rollout=rollout, plies=plies, line_padded=True))
+    assert n > 0
