@@ -345,6 +345,7 @@ def bench_go(args, cfg):
         start_dev = None if start is None else torch.as_tensor(start, device="cuda")
         bufs = go_rollout_buffers(torch, S, B, pitches, with_obs)
         env.rollout(pre + Wm, seed, 0, start_t=start_dev, slices=S, **bufs)
+        ev0.record(); ev1.record()                # torch creates the HIP events at their first record: not inside the timed region
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record()
@@ -364,13 +365,15 @@ def bench_go(args, cfg):
         st = GoStepper(cfg, B, with_obs, fused=(args.mode == "fused"), superko=args.superko, line_padded=args.line_padded)
         st.preroll(pre)
         st.run(Wm)
-        torch.cuda.synchronize()
         first = st.t
         # the timed region, cut into five segments by events on the same stream (median and best segment are reported too)
         # (only when there are enough launches that the four extra event records between them do not matter)
         nseg = 5 if K >= 100 else 1
         cuts = [K * i // nseg for i in range(nseg + 1)]
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(nseg - 1)]
+        for e in [ev0, ev1] + marks:              # torch creates the HIP events at their first record: not inside the timed region
+            e.record()
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record()
         for i in range(nseg):
@@ -521,6 +524,7 @@ def bench_hex(args, cfg):
                     mask=mask.view(1, B, 122), obs=None if obs is None else obs.view(1, B, 484))
         if Wm:
             env.rollout(Wm, seed, pre, **bufs)
+        ev0.record(); ev1.record()                # created at their first record: not inside the timed region
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record()
@@ -534,6 +538,7 @@ def bench_hex(args, cfg):
         env.random_actions(seed, pre, out=acts[pre & 1])
         for t in range(pre, pre + Wm):
             env.step_sample(acts[t & 1], seed, t + 1, out=acts[(t + 1) & 1])
+        ev0.record(); ev1.record()                # created at their first record: not inside the timed region
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         ev0.record()
