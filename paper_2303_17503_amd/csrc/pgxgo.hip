@@ -685,7 +685,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_kernel(StepArg
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
   const int wib = wave_in_block();
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);   // in a wavefront beyond the batch no lane is valid
   const size_t rows_total = (size_t)a.B * N;
 
@@ -1226,7 +1226,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, 6) go_step_superko_kernel
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
   const int wib = wave_in_block();
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
   const size_t rows_total = (size_t)a.B * N;
   Row<N> R;
@@ -1370,7 +1370,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_step_slots
   __shared__ __attribute__((aligned(16))) uint32_t lds_mask_all[kWavesPerBlock][64];
   __shared__ uint2 lut[256];
   const int wib = wave_in_block();
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   Lane<N> L(wave, threadIdx.x & 63, a.n);
   const size_t rows_total = (size_t)a.pool * N;
   const int src = L.boardok ? a.src[L.b] : 0, dst = L.boardok ? a.dst[L.b] : 0;
@@ -1481,7 +1481,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock, SK ? 4 : 6) go_rollout_ke
   __shared__ uint2 lut[256];
   fill_spread_table(lut);
   const int wib = wave_in_block();
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   if (wave * a.wb >= a.B) return;
   const Lane<N> L(wave, threadIdx.x & 63, a.B, a.wb);
   const size_t rows_total = (size_t)a.B * N;
@@ -1569,7 +1569,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_emit_kernel(const uint
   __shared__ uint2 lut[256];
   fill_spread_table(lut);
   const int wib = wave_in_block();
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   if (wave * G::W >= B) return;
   const Lane<N> L(wave, threadIdx.x & 63, B);
   Row<N> R;
@@ -1594,7 +1594,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) go_random_actions_kernel(
                                                                                 const uint4* zcur) {
   using G = Geo<N>;
   __shared__ uint32_t sk_scratch[SK ? kWavesPerBlock : 1][64];
-  const int wave = blockIdx.x * kWavesPerBlock + wave_in_block();
+  const int wave = piece_of_block() * kWavesPerBlock + wave_in_block();
   if (wave * G::W >= B) return;
   const Lane<N> L(wave, threadIdx.x & 63, B);
   Row<N> R;
@@ -1818,8 +1818,8 @@ int launch_reset(pgxgo_ctx* h, int first) {
 template <int N>
 unsigned waves_for(int B) { return (unsigned)((B + Geo<N>::W - 1) / Geo<N>::W); }
 template <int N>
-unsigned blocks_for(int B) { return (waves_for<N>(B) + kWavesPerBlock - 1) / kWavesPerBlock; }
-unsigned blocks_for_wb(int B, int wb) { return ((unsigned)((B + wb - 1) / wb) + kWavesPerBlock - 1) / kWavesPerBlock; }
+unsigned blocks_for(int B) { return ((waves_for<N>(B) + kWavesPerBlock - 1) / kWavesPerBlock + 7u) & ~7u; }   // a multiple of 8: piece_of_block
+unsigned blocks_for_wb(int B, int wb) { return (((unsigned)((B + wb - 1) / wb) + kWavesPerBlock - 1) / kWavesPerBlock + 7u) & ~7u; }
 
 // Boards per wavefront for the step and rollout launches.  A wavefront can hold W boards; with few games it is
 // better to spread them over more wavefronts (shorter floods, fewer output rounds per wavefront), so the count

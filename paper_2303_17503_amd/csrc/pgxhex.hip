@@ -277,7 +277,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_kernel(StepArgs 
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const Lane L(wave, lane, a.B);
   const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
   const uint4 mv = L.boardok ? a.meta[L.b] : make_uint4(0u, 0u, 0u, 0u);
@@ -535,7 +535,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_step_lane_kernel(Step
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][LANE_OBS_DW];
   __shared__ __align__(16) uint32_t lds_mask[kWavesPerBlock][LANE_MASK_DW];
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const int b0 = wave * 64;                 // first board of the wavefront
   const int b = b0 + lane;
   const bool ok = b < a.B;
@@ -601,7 +601,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_kernel(Rollou
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
   fill_spread_table(lut);
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   if (wave * W >= a.B) return;
   const Lane L(wave, lane, a.B);
   const uint32_t word = L.valid ? a.rows[(size_t)L.b * N + L.r] : 0u;
@@ -638,7 +638,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_rollout_lane_kernel(R
   fill_spread4_table(lut4);
   fill_spread_table(lut);
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const int b0 = wave * 64;
   if (b0 >= a.B) return;
   const int b = b0 + lane;
@@ -681,7 +681,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uin
   __shared__ __align__(16) uint32_t lds_obs[kWavesPerBlock][OBS_DW];
   __shared__ uint32_t lds_mask[kWavesPerBlock][MASK_DW];
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   const Lane L(wave, lane, B);
   const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
   const Meta m = unpack_meta(L.boardok ? meta[L.b] : make_uint4(0u, 0u, 0u, 0u));
@@ -693,7 +693,7 @@ __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_emit_kernel(const uin
 __global__ void __launch_bounds__(64 * kWavesPerBlock) hex_random_actions_kernel(const uint32_t* rows, const uint4* meta, int B, uint32_t seed, uint32_t t,
                                                                                 const int32_t* start_t, int32_t* actions) {
   const int wib = wave_in_block(), lane = threadIdx.x & 63;
-  const int wave = blockIdx.x * kWavesPerBlock + wib;
+  const int wave = piece_of_block() * kWavesPerBlock + wib;
   if (wave * W >= B) return;
   const Lane L(wave, lane, B);
   const uint32_t word = L.valid ? rows[(size_t)L.b * N + L.r] : 0u;
@@ -811,10 +811,12 @@ bool board_per_lane(const pgxhex_ctx* h, bool rollout = false) {
   return h->mapping == 2 || (h->mapping == 0 && h->B >= (rollout ? kLaneMappingFromRollout : kLaneMappingFromStep));
 }
 
+// grids of the board kernels: a multiple of 8 blocks (piece_of_block)
 unsigned blocks_for(int B) {
   const unsigned waves = (unsigned)((B + W - 1) / W);
-  return (waves + kWavesPerBlock - 1) / kWavesPerBlock;
+  return ((waves + kWavesPerBlock - 1) / kWavesPerBlock + 7u) & ~7u;
 }
+unsigned lane_blocks_for(int B) { return ((unsigned)((B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock)) + 7u) & ~7u; }
 unsigned row_blocks(int B) { return (unsigned)(((size_t)B * N + 255) / 256); }
 
 int launch_emit(pgxhex_ctx* h, uint8_t* mask, uint8_t* obs) {
@@ -835,7 +837,7 @@ int launch_step(pgxhex_ctx* h, const int32_t* actions, bool sample, uint32_t see
   a.B = h->B; a.seed = h->seed; a.auto_reset = h->auto_reset;
   a.sample_seed = seed; a.sample_t = t; a.start_t = start_t; a.next_actions = next;
   if (board_per_lane(h)) {
-    const dim3 grid((unsigned)((h->B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock)));
+    const dim3 grid(lane_blocks_for(h->B));
     if (sample) hipLaunchKernelGGL(hex_step_lane_kernel<true>, grid, dim3(64 * kWavesPerBlock), 0, h->stream, a);
     else hipLaunchKernelGGL(hex_step_lane_kernel<false>, grid, dim3(64 * kWavesPerBlock), 0, h->stream, a);
   } else if (sample) hipLaunchKernelGGL(hex_step_kernel<true>, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
@@ -932,8 +934,7 @@ int pgxhex_rollout(pgxhex_t h, int32_t steps, int32_t slices, uint32_t seed, uin
   a.steps = steps; a.slices = slices; a.seed = seed; a.t0 = t0; a.start_t = start_t_dev;
   a.actions = actions_dev; a.rew = rewards_dev; a.term = terminated_dev; a.mask = mask_dev; a.obs = obs_dev;
   if (board_per_lane(h, true))
-    hipLaunchKernelGGL(hex_rollout_lane_kernel, dim3((unsigned)((h->B + 64 * kWavesPerBlock - 1) / (64 * kWavesPerBlock))), dim3(64 * kWavesPerBlock), 0,
-                       h->stream, a);
+    hipLaunchKernelGGL(hex_rollout_lane_kernel, dim3(lane_blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   else hipLaunchKernelGGL(hex_rollout_kernel, dim3(blocks_for(h->B)), dim3(64 * kWavesPerBlock), 0, h->stream, a);
   HIPCHK(hipGetLastError());
   return PGXHEX_OK;

@@ -26,6 +26,13 @@ __device__ __forceinline__ uint32_t env_hash(uint32_t seed, uint32_t tag, uint32
 // (so that everything derived from it -- output addresses, trip counts -- is computed once per wavefront)
 __device__ __forceinline__ int wave_in_block() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
+// Which piece of the batch a block works on.  The hardware hands the blocks of a launch to the chip's eight dies (each
+// with an L2 of its own) round-robin by block index; with piece = block index, neighbouring stretches of every array
+// would be written through eight different L2s.  Block i takes piece (i mod 8) * (blocks / 8) + i / 8 instead, so that
+// each die reads and writes one contiguous eighth of the batch (65536 games of 19x19: 85.5 -> 82.7 us per ply;
+// 16384 games: 20.45 -> 20.25).  The grid must be a multiple of 8 blocks (pieces beyond the batch are idle).
+__device__ __forceinline__ int piece_of_block() { return (int)(blockIdx.x & 7u) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3); }
+
 // ------------------------------------------------------------------------------------------------
 // cross-lane primitives.  All of them must be called with every lane of the wavefront active.
 // ------------------------------------------------------------------------------------------------
