@@ -28,9 +28,11 @@ __device__ __forceinline__ int wave_in_block() { return __builtin_amdgcn_readfir
 
 // Which piece of the batch a block works on.  The hardware hands the blocks of a launch to the chip's eight dies (each
 // with an L2 of its own) round-robin by block index; with piece = block index, neighbouring stretches of every array
-// would be written through eight different L2s.  Block i takes piece (i mod 8) * (blocks / 8) + i / 8 instead, so that
-// each die reads and writes one contiguous eighth of the batch (65536 games of 19x19: 85.5 -> 82.7 us per ply;
-// 16384 games: 20.45 -> 20.25).  The grid must be a multiple of 8 blocks (pieces beyond the batch are idle).
+// would be written through eight different L2s, and a 128-byte line shared by the output runs of two neighbouring
+// blocks would reach memory as two partial writes.  Block i takes piece (i mod 8) * (blocks / 8) + i / 8 instead, so
+// that each die reads and writes one contiguous eighth of the batch and such lines leave one L2 whole (65536 games of
+// 19x19: 85.5 -> 82.5 us per ply; 16384 games: 20.4 -> 20.15).  The grid must be a multiple of 8 blocks (pieces
+// beyond the batch are idle).
 __device__ __forceinline__ int piece_of_block() { return (int)(blockIdx.x & 7u) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3); }
 
 // ------------------------------------------------------------------------------------------------
