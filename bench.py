@@ -452,6 +452,9 @@ def bench_go(args, cfg):
                      "dram": dram, "fill": fill, "launch_gap_us": gap_us,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
     }
+    if traffic:
+        # the fill's time scaled from the output bytes to the bytes the counters saw this kernel move (state included)
+        out["roofline"]["frac_of_fill_at_traffic"] = fill["in_place_ms"] * traffic / out_bytes / kern_ms
     if seg_ms:
         out["roofline"]["kernel_ms_segments"] = seg_ms
         out["roofline"]["kernel_ms_median"] = sorted(seg_ms)[2]
