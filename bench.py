@@ -589,6 +589,8 @@ def bench_hex(args, cfg):
                      "frac_of_fill": fill["in_place_ms"] / kern_ms, "dram": dram, "fill": fill, "launch_gap_us": gap_us,
                      "whole_step_gbs": bytes_ply * B * K / wall / 1e9, "device_copy_gbs": copy_gbs},
     }
+    if traffic:   # the fill's time scaled from the output bytes to the bytes the counters saw this kernel move
+        out["roofline"]["frac_of_fill_at_traffic"] = fill["in_place_ms"] * traffic / out_bytes / kern_ms
     if args.mode == "fused":
         tiny = pg.HexEnv(5, seed=seed, auto_reset=cfg.auto_reset)
         tm, to = tiny.new_mask(), tiny.new_obs() if with_obs else None
