@@ -306,6 +306,23 @@ def test_full_size_configurations(k):
     assert p.n_compared == (cfg.batch if ids is None else len(ids)) * plies
 
 
+@pytest.mark.parametrize("mapping", [1, 2])
+def test_outputs_beyond_four_gibibytes(mapping):
+    """8900003 games: the observation tensor is 4.31 GB, so the byte offsets of the last 26000 games do not fit 32 bits,
+    and the batch is no multiple of a wavefront's games.  The oracle replays the first games, the games on both sides of
+    the 4 GiB offset and the last ones, in both lane mappings."""
+    B, seed, T = 8900003, 17, 24
+    cross = (1 << 32) // OBS
+    ids = np.concatenate([np.arange(0, 320), np.arange(cross - 160, cross + 160), np.arange(B - 320, B)])
+    p = HexPair(B, seed=seed, auto_reset=True, ids=ids, mapping=mapping)
+    assert p.obs.numel() > (1 << 32)
+    p.rollout(seed, 0, T, fused=True, state_every=12)
+    assert p.n_compared == len(ids) * T
+    assert bool((p.mask.sum(dim=1) > 0).all())          # every game has a legal action
+    del p
+    torch.cuda.empty_cache()
+
+
 def alloc_traj(S, B):
     return dict(actions=torch.empty((S, B), dtype=torch.int32, device="cuda"),
                 rewards=torch.empty((S, B, 2), dtype=torch.float32, device="cuda"),

@@ -254,6 +254,49 @@ def test_benchmark_configs_full_size(ci):
         assert bool((g["terminated"] == 1).all())
 
 
+def test_outputs_beyond_four_gibibytes():
+    """720001 games of 19x19: the observation tensor is 4.42 GB, so the byte offsets of the last 20000 games do not fit
+    32 bits; the batch is not a multiple of the boards of a wavefront or of a block.  The oracle replays the first games,
+    the games on both sides of the 4 GiB offset and the last ones, every tenth ply of 150."""
+    from gpu_common import Pair
+    B, N, seed, T = 720001, 19, 11, 150
+    cross = (1 << 32) // (N * N * 17)      # the game whose observation straddles the 4 GiB offset
+    ids = np.concatenate([np.arange(0, 384), np.arange(cross - 192, cross + 192), np.arange(B - 384, B)]).astype(np.int32)
+    p = Pair(B, N, seed=seed, auto_reset=True, ids=ids)
+    assert p.obs.numel() > (1 << 32)
+    p.rollout(seed, 0, T, every=10, state_every=50, fused=True)
+    assert p.n_actions == len(ids) * T
+    g = p.env.export_state()
+    P = N * N
+    assert bool((p.mask[:, P] == 1).all())
+    assert bool(((p.mask[:, :P] == 1) & (g["board"] != 0)).sum() == 0)
+    obs = p.obs.view(B, P, 17)
+    assert bool(((obs[:, :, 0] + obs[:, :, 1]) == (g["board"] != 0)).all())
+    stones = int((g["board"] != 0).sum())
+    assert stones > 60 * B                 # boards have filled up (about 100 stones after 150 plies)
+    del g, obs
+    # the rollout kernel on the same games, two output slices (the second one starts 4.4 GB after the first)
+    env, orc, sel = p.env, p.orc, p.sel
+    acts = torch.empty((2, B), dtype=torch.int32, device="cuda")
+    rew = torch.empty((2, B, 2), dtype=torch.float32, device="cuda")
+    term = torch.empty((2, B), dtype=torch.uint8, device="cuda")
+    mask = torch.empty((2, B, P + 1), dtype=torch.uint8, device="cuda")
+    obs2 = torch.empty((2, B, P * 17), dtype=torch.uint8, device="cuda")
+    env.rollout(6, seed, T, slices=2, actions=acts, rewards=rew, terminated=term, mask=mask, obs=obs2)
+    for i in range(6):
+        a = orc.random_actions(seed, T + i)
+        orc.step(a)
+        if i >= 4:                         # the last two plies are still in the slices (ply i -> slice i % 2)
+            k = i & 1
+            assert (acts[k].index_select(0, sel).cpu().numpy() == a).all(), i
+            assert (mask[k].index_select(0, sel).cpu().numpy() == orc.legal_mask()).all(), i
+            assert (obs2[k].index_select(0, sel).cpu().numpy().reshape(-1, N, N, 17) == orc.observe()).all(), i
+            assert (rew[k].index_select(0, sel).cpu().numpy() == orc.rewards()).all(), i
+            assert (term[k].index_select(0, sel).cpu().numpy() == orc.terminated()).all(), i
+    del p, env, acts, rew, term, mask, obs2
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("N,B,T,slices,auto_reset", [(9, 100, 200, 200, True), (19, 50, 300, 300, True), (19, 64, 120, 1, False), (9, 13, 90, 7, True)])
 def test_rollout_kernel_equals_stepwise_play(N, B, T, slices, auto_reset):
     """One launch of `T` plies (state kept in registers) against the oracle stepping ply by ply: every slice of
