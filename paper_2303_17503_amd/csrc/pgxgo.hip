@@ -1845,9 +1845,13 @@ size_t output_bytes_per_ply(const pgxgo_ctx* h, bool with_mask, bool with_obs) {
   return (size_t)h->B * ((with_mask ? (size_t)h->mask_pitch : 0) + (with_obs ? (size_t)h->obs_pitch : 0));
 }
 
+// One board per wavefront while every wavefront can have a SIMD to itself (1024 SIMDs), then as many boards per
+// wavefront as keep it at one wavefront per SIMD, up to W (measured per ply, one launch per ply, best / worst choice:
+// 9x9 x 2048 games 6.9 us with 2 boards against 7.5 with 1; x 4096 7.4 with 4 against 9.5 with 1; x 6144 7.7 with 6
+// against 11.6 with 1; 19x19 x 3072 8.9 with 3 against 10.3 with 1).
 template <int N>
 int auto_boards_per_wavefront(int B) {
-  const int want = (B + 2047) / 2048;
+  const int want = (B + 1023) / 1024;
   return want < 1 ? 1 : (want > Geo<N>::W ? Geo<N>::W : want);
 }
 
